@@ -1,0 +1,170 @@
+/* losa.h — C ABI of the LoSA prefix-attention hot path for AMD MI355X (gfx950).
+ *
+ * One denoising step of a block-wise diffusion LM, per layer (paper: Methodology;
+ * Fig. MethodOverview steps i-iii):
+ *   (i)   locality score per block token and the active set A      -> losa_select_active
+ *   (ii)  QUEST page bounds, per-query top pages, union per KV head -> losa_page_bounds, losa_score_pages
+ *   (iii) prefix attention of the active queries over the union; stable tokens keep
+ *         their cached (o_p, L_p)                                   -> losa_sparse_attn
+ *   the three chained, with the dense initialisation at step 0     -> losa_step
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless marked host.  The caller owns every
+ *     buffer (inputs, outputs, page metadata, workspace); the library allocates no
+ *     device memory and keeps no caller pointer after a call returns, except the
+ *     workspace handed to losa_create, which it uses until losa_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work; they never synchronise.  Counts (active tokens, union sizes)
+ *     stay on the device.
+ *   - Element type T of h, q, K, V and the page metadata is bfloat16 (LOSA_BF16) or
+ *     float (LOSA_F32), fixed at losa_create.  Accumulation is float.  The cached
+ *     prefix statistics o_p and lse_p are float in both modes.
+ *   - Shapes use the paper's symbols: B block size, d head dim, g page size,
+ *     Hq / Hkv query / KV heads, G = Hq/Hkv, H hidden size, P_b pages of sequence b.
+ *     Arrays are row-major with the last index fastest.
+ *   - Return value: LOSA_OK, or an error found by host-side validation before anything
+ *     was enqueued (LOSA_ERR_INVALID_ARG, LOSA_ERR_UNSUPPORTED, LOSA_ERR_WORKSPACE), or
+ *     LOSA_ERR_HIP if a launch was rejected.  losa_last_error gives the text.  Nothing
+ *     throws or aborts.  Device-side indices (page ids, token ids) outside their range
+ *     are skipped by the kernels, never dereferenced.
+ *   - Calls on one losa_ctx share its workspace: issue them on one stream, or
+ *     serialise them.
+ */
+#ifndef LOSA_H
+#define LOSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct losa_ctx losa_ctx; /* opaque, host memory */
+
+typedef enum {
+  LOSA_OK = 0,
+  LOSA_ERR_INVALID_ARG = 1,
+  LOSA_ERR_UNSUPPORTED = 2,
+  LOSA_ERR_WORKSPACE = 3,
+  LOSA_ERR_HIP = 4
+} losa_status;
+
+typedef enum { LOSA_BF16 = 0, LOSA_F32 = 1 } losa_dtype;
+
+/* How the active set is chosen from the locality scores (Methodology, Locality Pruning):
+ * TOPK: the `param` tokens with the largest score (the paper's rule; it uses 5 of 16);
+ * FRACTION: top n with n = max(1, floor(param*B + 0.5));  THRESHOLD: score > param.
+ * Ties: larger score first, then smaller token index. */
+typedef enum { LOSA_SEL_TOPK = 0, LOSA_SEL_FRACTION = 1, LOSA_SEL_THRESHOLD = 2 } losa_select_mode;
+
+typedef struct {
+  int32_t max_batch;         /* sequences per call, >= 1 */
+  int32_t num_q_heads;       /* Hq */
+  int32_t num_kv_heads;      /* Hkv, divides Hq */
+  int32_t head_dim;          /* d: 64 or 128 */
+  int32_t hidden_size;       /* H: row length of the tensor the detector compares; multiple of 8 */
+  int32_t page_size;         /* g: 16 or 32 */
+  int32_t block_size;        /* B: 1..256 */
+  int32_t max_pages_per_seq; /* upper bound on P_b */
+  int32_t max_topk_pages;    /* upper bound on the per-query page budget K = k/g */
+  int32_t dtype;             /* losa_dtype */
+  float sm_scale;            /* score scale; 0 means 1/sqrt(d) */
+} losa_config;
+
+/* Ragged paged prefix KV cache of one layer (K_p, V_p of the paper, fixed across the
+ * denoising steps of a block).  A page-head tile of keys is token-major, a tile of
+ * values is channel-major (V is stored transposed inside each page), which is the
+ * operand order the matrix cores consume without a shuffle. */
+typedef struct {
+  const void* k_pages;         /* T [num_pages, Hkv, g, d] */
+  const void* v_pages;         /* T [num_pages, Hkv, d, g] */
+  void* meta;                  /* T [num_pages, Hkv, 2, d]: row 0 elementwise min key, row 1 max key.
+                                  Written by losa_page_bounds, read by losa_score_pages / losa_step. */
+  const int32_t* page_indptr;  /* [batch+1] offsets into page_indices; P_b = indptr[b+1]-indptr[b] */
+  const int32_t* page_indices; /* logical page p of sequence b -> physical page id */
+  const int32_t* seq_lens;     /* [batch] prefix tokens L_b; the last page may be partly filled;
+                                  slots past L_b may hold anything (NaN included) */
+  int32_t batch;               /* host: 1..max_batch */
+  int32_t num_pages;           /* host: pages in the pool (ids >= num_pages are skipped) */
+  int32_t max_seq_pages;       /* host: max_b P_b if known, else 0 (= max_pages_per_seq) */
+} losa_kv;
+
+/* Bytes of device workspace losa_create needs for this configuration (0 if it is invalid). */
+size_t losa_workspace_bytes(const losa_config* cfg);
+
+/* Validates cfg, takes `workspace` (device, 256-byte aligned, >= losa_workspace_bytes) and
+ * returns a context in *out.  Enqueues nothing. */
+losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspace_bytes, losa_ctx** out);
+losa_status losa_destroy(losa_ctx* ctx);
+/* Text of the last error on this context (host string owned by the context);
+ * with ctx == NULL, the text of the last losa_create failure of this thread. */
+const char* losa_last_error(const losa_ctx* ctx);
+
+/* (i) Locality score and active set (eq. mse_locality; Locality Pruning).
+ * delta[r] = mean_c (h_cur[r,c] - h_prev[r,c])^2 for each of the batch*B rows.
+ *   h_cur, h_prev : T [batch*B, H]
+ *   delta         : float [batch*B]
+ *   mask          : uint8 [batch*B], 1 = active
+ *   active_idx    : int32 [batch*B]; for sequence b, entries [b*B, b*B+count) are the active
+ *                   token ids (0..B-1) ascending, the rest -1
+ *   active_count  : int32 [batch] */
+losa_status losa_select_active(losa_ctx* ctx, void* stream, int32_t batch,
+                               const void* h_cur, const void* h_prev,
+                               losa_select_mode mode, float param,
+                               float* delta, uint8_t* mask, int32_t* active_idx, int32_t* active_count);
+
+/* (ii-a) QUEST page metadata (Preliminaries, Sparse Attention Algorithms): elementwise
+ * min and max key over the valid tokens of each page, for logical pages
+ * [first_logical_page, first_logical_page + num_logical_pages) of every sequence
+ * (num_logical_pages < 0: to the end).  Run once when pages are appended, not per step:
+ * the prefix is fixed across the denoising steps of a block.  Writes kv->meta. */
+losa_status losa_page_bounds(losa_ctx* ctx, void* stream, const losa_kv* kv,
+                             int32_t first_logical_page, int32_t num_logical_pages);
+
+/* (ii-b) Page scores, per-query top pages and their union (QUEST upper bound; eq. quest_union).
+ * For every active token i, query head h (KV head j = h / G) and logical page p:
+ *   s = sum_c max(q_c * min_{p,j,c}, q_c * max_{p,j,c});
+ * the min(topk_pages, P_b) pages with the largest s are picked (ties: smaller page), and
+ * the union over the active queries of a KV head is emitted ascending.
+ *   q          : T [batch*B, Hq, d]
+ *   active_idx, active_count : as written by losa_select_active
+ *   topk_out   : nullable int32 [batch, B, Hq, topk_pages]; slot a of sequence b (its a-th
+ *                active token) gets the picked pages ascending, padded with -1
+ *   sel_pages  : int32 [batch, Hkv, cap] logical pages, ascending
+ *   sel_count  : int32 [batch, Hkv]
+ *   cap        : >= min(max P_b, B*G*topk_pages)  (the union's worst case) */
+losa_status losa_score_pages(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q,
+                             const int32_t* active_idx, const int32_t* active_count,
+                             int32_t topk_pages, int32_t* topk_out,
+                             int32_t* sel_pages, int32_t* sel_count, int32_t cap);
+
+/* (iii) Prefix attention of the active queries over the selected pages (Attention
+ * Decomposition With Online Softmax; eq. update_rule).  For each active token i and head h:
+ *   s_t = sm_scale * q . k_t over the valid tokens t of the pages of its KV head's list,
+ *   lse_p[i,h] = ln sum_t exp(s_t),   o_p[i,h,:] = sum_t exp(s_t - lse_p) v_t.
+ * Rows of tokens that are not active are not touched (eq. reuse_rule).
+ *   active_idx, active_count : both NULL = every token of the block is active
+ *   sel_pages, sel_count     : both NULL = every page (dense prefix attention)
+ *   o_p   : float [batch*B, Hq, d]  in/out
+ *   lse_p : float [batch*B, Hq]     in/out (natural log)
+ * A sequence with no selected token gives o_p = 0, lse_p = -inf for its active rows. */
+losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q,
+                             const int32_t* active_idx, const int32_t* active_count,
+                             const int32_t* sel_pages, const int32_t* sel_count, int32_t cap,
+                             void* o_p, float* lse_p);
+
+/* One denoising step: step_index 0 = dense initialisation (all tokens, all pages; h_* unused
+ * and may be NULL); otherwise (i) -> (ii-b) -> (iii) chained on `stream` with the
+ * intermediate lists kept in the workspace.  The caller swaps h_cur / h_prev afterwards.
+ *   mask      : nullable uint8 [batch*B]  (diagnostic: the active mask; untouched at step 0)
+ *   sel_count : nullable int32 [batch, Hkv] (diagnostic: union sizes in pages; untouched at step 0) */
+losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t step_index,
+                      const void* h_cur, const void* h_prev, const void* q,
+                      losa_select_mode mode, float param, int32_t topk_pages,
+                      void* o_p, float* lse_p, uint8_t* mask, int32_t* sel_count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOSA_H */

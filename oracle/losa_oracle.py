@@ -223,9 +223,15 @@ def losa_step(cache: PrefixCache, step_index: int,
                         picks.append(I_ih)
                 I = union_pages(picks)
             tr.union[(b, j)] = I
-            if len(A) == 0 or len(I) == 0:
+            if len(A) == 0:
                 continue
             tok = tokens_of_pages(I, cache.g, cache.L[b])
+            if len(tok) == 0:
+                # attention over an empty key set: the neutral element of the online-softmax merge
+                for h in heads:
+                    o_p[b * B + A, h] = 0.0
+                    L_p[b * B + A, h] = -np.inf
+                continue
             K_sel, V_sel = cache.K[b][tok, j], cache.V[b][tok, j]
             for h in heads:
                 o, lse = prefix_attention(qf[b * B + A, h], K_sel, V_sel, scale)

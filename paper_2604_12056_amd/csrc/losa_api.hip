@@ -1,0 +1,365 @@
+// C ABI of liblosa.so: context, host-side validation, workspace carving and the launch
+// sequences.  No device memory is allocated here; every call only enqueues kernels.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "losa_internal.h"
+
+using namespace losa;
+
+struct losa_ctx {
+  losa_config cfg;
+  Shape sh;
+  // workspace carve (device pointers)
+  float* delta;
+  uint8_t* mask;
+  int32_t* active_idx;
+  int32_t* active_count;
+  float* scores;
+  uint32_t* bitmap;
+  int32_t* sel_pages;
+  int32_t* sel_count;
+  Partials part;
+  long part_items;
+  char err[256];
+};
+
+namespace {
+
+constexpr long kTargetItems = 1024;  // split-K work items aimed at per attention launch (4 per CU)
+constexpr int kMinChunkPages = 2;
+
+thread_local char g_create_err[256] = "";
+
+losa_status fail(losa_ctx* ctx, losa_status st, const char* fmt, ...) {
+  char* dst = ctx ? ctx->err : g_create_err;
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(dst, 256, fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+bool config_problem(const losa_config* c, char* why, size_t n) {
+#define BAD(cond, msg)            \
+  if (cond) {                     \
+    snprintf(why, n, "%s", msg);  \
+    return true;                  \
+  }
+  BAD(!c, "config is NULL");
+  BAD(c->max_batch < 1, "max_batch must be >= 1");
+  BAD(c->num_q_heads < 1 || c->num_kv_heads < 1, "head counts must be >= 1");
+  BAD(c->num_q_heads % c->num_kv_heads != 0, "num_q_heads must be a multiple of num_kv_heads");
+  BAD(c->head_dim != 64 && c->head_dim != 128, "head_dim must be 64 or 128");
+  BAD(c->page_size != 16 && c->page_size != 32, "page_size must be 16 or 32");
+  BAD(c->block_size < 1 || c->block_size > 256, "block_size must be in 1..256");
+  BAD(c->hidden_size < 8 || c->hidden_size % 8 != 0, "hidden_size must be a positive multiple of 8");
+  BAD(c->max_pages_per_seq < 1, "max_pages_per_seq must be >= 1");
+  BAD(c->max_topk_pages < 1, "max_topk_pages must be >= 1");
+  BAD(c->dtype != LOSA_BF16 && c->dtype != LOSA_F32, "dtype must be LOSA_BF16 or LOSA_F32");
+  BAD(!(c->sm_scale >= 0.f) || isinf(c->sm_scale), "sm_scale must be finite and >= 0");
+  BAD((long)c->block_size * (c->num_q_heads / c->num_kv_heads) > 4096, "block_size * group size must be <= 4096");
+#undef BAD
+  return false;
+}
+
+struct Carve {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    const size_t at = off;
+    off = align256(off + bytes);
+    return at;
+  }
+};
+
+struct Layout {
+  size_t delta, mask, active_idx, active_count, scores, bitmap, sel_pages, sel_count, po, pm, pl, total;
+  long part_items;
+};
+
+Layout make_layout(const losa_config* c) {
+  Layout L;
+  Carve cv;
+  const size_t rows = (size_t)c->max_batch * c->block_size;
+  const size_t G = c->num_q_heads / c->num_kv_heads;
+  const size_t rows_max = (size_t)c->block_size * G;
+  const size_t heads = (size_t)c->max_batch * c->num_kv_heads;
+  const size_t words = ((size_t)c->max_pages_per_seq + 31) / 32;
+  L.part_items = (long)heads > kTargetItems ? (long)heads : kTargetItems;
+  L.delta = cv.take(rows * 4);
+  L.mask = cv.take(rows);
+  L.active_idx = cv.take(rows * 4);
+  L.active_count = cv.take((size_t)c->max_batch * 4);
+  L.scores = cv.take(heads * rows_max * c->max_pages_per_seq * 4);
+  L.bitmap = cv.take(heads * words * 4);
+  L.sel_pages = cv.take(heads * c->max_pages_per_seq * 4);
+  L.sel_count = cv.take(heads * 4);
+  L.po = cv.take((size_t)L.part_items * rows_max * c->head_dim * 4);
+  L.pm = cv.take((size_t)L.part_items * rows_max * 4);
+  L.pl = cv.take((size_t)L.part_items * rows_max * 4);
+  L.total = cv.off;
+  return L;
+}
+
+hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+losa_status check_kv(losa_ctx* ctx, const losa_kv* kv, bool need_meta, int* max_seq_pages) {
+  if (!kv) return fail(ctx, LOSA_ERR_INVALID_ARG, "kv is NULL");
+  if (kv->batch < 1 || kv->batch > ctx->cfg.max_batch)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.batch %d outside 1..max_batch (%d)", kv->batch, ctx->cfg.max_batch);
+  if (!kv->k_pages || !kv->v_pages || !kv->page_indptr || !kv->page_indices || !kv->seq_lens)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "kv has a NULL device pointer");
+  if (need_meta && !kv->meta) return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.meta is NULL");
+  if (kv->num_pages < 0) return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.num_pages is negative");
+  if (kv->max_seq_pages < 0 || kv->max_seq_pages > ctx->cfg.max_pages_per_seq)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.max_seq_pages %d outside 0..max_pages_per_seq (%d)", kv->max_seq_pages,
+                ctx->cfg.max_pages_per_seq);
+  *max_seq_pages = kv->max_seq_pages > 0 ? kv->max_seq_pages : ctx->cfg.max_pages_per_seq;
+  return LOSA_OK;
+}
+
+KvView view_of(const losa_kv* kv) {
+  KvView v;
+  v.k_pages = kv->k_pages;
+  v.v_pages = kv->v_pages;
+  v.meta = kv->meta;
+  v.page_indptr = kv->page_indptr;
+  v.page_indices = kv->page_indices;
+  v.seq_lens = kv->seq_lens;
+  v.num_pages = kv->num_pages;
+  return v;
+}
+
+losa_status hip_fail(losa_ctx* ctx, const char* what, hipError_t e) {
+  return fail(ctx, LOSA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// Number of page chunks per (sequence, KV head) list of at most `upper` pages.
+void pick_chunks(const losa_ctx* ctx, int batch, int upper, int* chunk_pages, int* nchunk) {
+  const long heads = (long)batch * ctx->sh.Hkv;
+  long want = ctx->part_items / heads;
+  if (want < 1) want = 1;
+  const int step = 32 / ctx->sh.g;  // whole 32-token tiles
+  long cp = (upper + want - 1) / want;
+  if (cp < kMinChunkPages) cp = kMinChunkPages;
+  cp = (cp + step - 1) / step * step;
+  *chunk_pages = (int)cp;
+  *nchunk = (int)((upper + cp - 1) / cp);
+  if (*nchunk < 1) *nchunk = 1;
+}
+
+losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const void* h_cur, const void* h_prev,
+                               int mode, float param, float* delta, uint8_t* mask, int32_t* active_idx,
+                               int32_t* active_count) {
+  const int B = ctx->sh.B;
+  int n = 0;
+  float tau = 0.f;
+  if (mode == LOSA_SEL_TOPK) {
+    if (!(param >= 0.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "top-k parameter must be >= 0");
+    n = param >= (float)B ? B : (int)param;
+  } else if (mode == LOSA_SEL_FRACTION) {
+    if (!(param >= 0.f && param <= 1.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "fraction must be in [0,1]");
+    n = (int)floorf(param * (float)B + 0.5f);
+    n = n < 1 ? 1 : (n > B ? B : n);
+  } else if (mode == LOSA_SEL_THRESHOLD) {
+    if (isnan(param)) return fail(ctx, LOSA_ERR_INVALID_ARG, "threshold is NaN");
+    tau = param;
+  } else {
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "unknown select mode %d", mode);
+  }
+  hipError_t e = launch_locality_delta(st, ctx->cfg.dtype, h_cur, h_prev, batch * B, ctx->sh.H, delta);
+  if (e != hipSuccess) return hip_fail(ctx, "locality_delta launch", e);
+  e = launch_rank_select(st, delta, batch, B, mode, n, tau, mask, active_idx, active_count);
+  if (e != hipSuccess) return hip_fail(ctx, "rank_select launch", e);
+  return LOSA_OK;
+}
+
+losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
+                             const void* q, const int32_t* active_idx, const int32_t* active_count, int topk,
+                             int32_t* topk_out, int32_t* sel_pages, int32_t* sel_count, int cap) {
+  hipError_t e = launch_page_scores(st, ctx->cfg.dtype, kv, ctx->sh, batch, max_seq_pages, q, active_idx,
+                                    active_count, ctx->scores, ctx->bitmap);
+  if (e != hipSuccess) return hip_fail(ctx, "page_scores launch", e);
+  e = launch_topk_union(st, kv, ctx->sh, batch, max_seq_pages, active_count, ctx->scores, topk, topk_out, ctx->bitmap);
+  if (e != hipSuccess) return hip_fail(ctx, "topk_union launch", e);
+  e = launch_union_compact(st, kv, ctx->sh, batch, max_seq_pages, active_count, ctx->bitmap, sel_pages, sel_count, cap);
+  if (e != hipSuccess) return hip_fail(ctx, "union_compact launch", e);
+  return LOSA_OK;
+}
+
+losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
+                             const void* q, const int32_t* active_idx, const int32_t* active_count,
+                             const int32_t* sel_pages, const int32_t* sel_count, int cap, float* o_p, float* lse_p) {
+  const int upper = sel_pages ? (cap < max_seq_pages ? cap : max_seq_pages) : max_seq_pages;
+  int chunk_pages, nchunk;
+  pick_chunks(ctx, batch, upper, &chunk_pages, &nchunk);
+  hipError_t e = launch_attn_partials(st, ctx->cfg.dtype, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages,
+                                      sel_count, cap, chunk_pages, nchunk, ctx->part);
+  if (e != hipSuccess) return hip_fail(ctx, "attn_partials launch", e);
+  e = launch_attn_merge(st, kv, ctx->sh, batch, active_idx, active_count, sel_count, cap, chunk_pages, nchunk,
+                        /*log2_units=*/false, ctx->part, o_p, lse_p);
+  if (e != hipSuccess) return hip_fail(ctx, "attn_merge launch", e);
+  return LOSA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t losa_workspace_bytes(const losa_config* cfg) {
+  char why[128];
+  if (config_problem(cfg, why, sizeof why)) return 0;
+  return make_layout(cfg).total;
+}
+
+losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspace_bytes, losa_ctx** out) {
+  if (!out) return fail(nullptr, LOSA_ERR_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  char why[128];
+  if (config_problem(cfg, why, sizeof why)) return fail(nullptr, LOSA_ERR_INVALID_ARG, "%s", why);
+  const Layout L = make_layout(cfg);
+  if (!workspace) return fail(nullptr, LOSA_ERR_WORKSPACE, "workspace is NULL");
+  if (((uintptr_t)workspace & 255u) != 0) return fail(nullptr, LOSA_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  if (workspace_bytes < L.total)
+    return fail(nullptr, LOSA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, L.total);
+  losa_ctx* ctx = new (std::nothrow) losa_ctx();
+  if (!ctx) return fail(nullptr, LOSA_ERR_INVALID_ARG, "out of host memory");
+  ctx->cfg = *cfg;
+  Shape& sh = ctx->sh;
+  sh.Hq = cfg->num_q_heads;
+  sh.Hkv = cfg->num_kv_heads;
+  sh.G = sh.Hq / sh.Hkv;
+  sh.d = cfg->head_dim;
+  sh.H = cfg->hidden_size;
+  sh.g = cfg->page_size;
+  sh.B = cfg->block_size;
+  sh.max_pages = cfg->max_pages_per_seq;
+  sh.rows_max = sh.B * sh.G;
+  sh.sm_scale = cfg->sm_scale > 0.f ? cfg->sm_scale : 1.0f / sqrtf((float)sh.d);
+  char* base = static_cast<char*>(workspace);
+  ctx->delta = (float*)(base + L.delta);
+  ctx->mask = (uint8_t*)(base + L.mask);
+  ctx->active_idx = (int32_t*)(base + L.active_idx);
+  ctx->active_count = (int32_t*)(base + L.active_count);
+  ctx->scores = (float*)(base + L.scores);
+  ctx->bitmap = (uint32_t*)(base + L.bitmap);
+  ctx->sel_pages = (int32_t*)(base + L.sel_pages);
+  ctx->sel_count = (int32_t*)(base + L.sel_count);
+  ctx->part.o = (float*)(base + L.po);
+  ctx->part.m = (float*)(base + L.pm);
+  ctx->part.l = (float*)(base + L.pl);
+  ctx->part_items = L.part_items;
+  ctx->err[0] = 0;
+  *out = ctx;
+  return LOSA_OK;
+}
+
+losa_status losa_destroy(losa_ctx* ctx) {
+  delete ctx;
+  return LOSA_OK;
+}
+
+const char* losa_last_error(const losa_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
+
+losa_status losa_select_active(losa_ctx* ctx, void* stream, int32_t batch, const void* h_cur, const void* h_prev,
+                               losa_select_mode mode, float param, float* delta, uint8_t* mask, int32_t* active_idx,
+                               int32_t* active_count) {
+  if (!ctx) return LOSA_ERR_INVALID_ARG;
+  if (batch < 1 || batch > ctx->cfg.max_batch)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "batch %d outside 1..max_batch (%d)", batch, ctx->cfg.max_batch);
+  if (!h_cur || !h_prev || !delta || !mask || !active_idx || !active_count)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_select_active: NULL pointer");
+  return select_active_impl(ctx, as_stream(stream), batch, h_cur, h_prev, (int)mode, param, delta, mask, active_idx,
+                            active_count);
+}
+
+losa_status losa_page_bounds(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t first_logical_page,
+                             int32_t num_logical_pages) {
+  if (!ctx) return LOSA_ERR_INVALID_ARG;
+  int msp;
+  losa_status s = check_kv(ctx, kv, true, &msp);
+  if (s != LOSA_OK) return s;
+  if (first_logical_page < 0) return fail(ctx, LOSA_ERR_INVALID_ARG, "first_logical_page is negative");
+  int n = msp - first_logical_page;
+  if (num_logical_pages >= 0 && num_logical_pages < n) n = num_logical_pages;
+  if (n <= 0) return LOSA_OK;
+  hipError_t e = launch_page_bounds(as_stream(stream), ctx->cfg.dtype, view_of(kv), ctx->sh, kv->batch,
+                                    first_logical_page, n);
+  if (e != hipSuccess) return hip_fail(ctx, "page_bounds launch", e);
+  return LOSA_OK;
+}
+
+losa_status losa_score_pages(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q, const int32_t* active_idx,
+                             const int32_t* active_count, int32_t topk_pages, int32_t* topk_out, int32_t* sel_pages,
+                             int32_t* sel_count, int32_t cap) {
+  if (!ctx) return LOSA_ERR_INVALID_ARG;
+  int msp;
+  losa_status s = check_kv(ctx, kv, true, &msp);
+  if (s != LOSA_OK) return s;
+  if (!q || !active_idx || !active_count || !sel_pages || !sel_count)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_score_pages: NULL pointer");
+  if (topk_pages < 1 || topk_pages > ctx->cfg.max_topk_pages)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "topk_pages %d outside 1..max_topk_pages (%d)", topk_pages,
+                ctx->cfg.max_topk_pages);
+  const long worst = (long)ctx->sh.rows_max * topk_pages;
+  const long need = worst < msp ? worst : msp;
+  if (cap < need) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap %d is below the union's worst case %ld", cap, need);
+  return score_pages_impl(ctx, as_stream(stream), view_of(kv), kv->batch, msp, q, active_idx, active_count,
+                          topk_pages, topk_out, sel_pages, sel_count, cap);
+}
+
+losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q, const int32_t* active_idx,
+                             const int32_t* active_count, const int32_t* sel_pages, const int32_t* sel_count,
+                             int32_t cap, void* o_p, float* lse_p) {
+  if (!ctx) return LOSA_ERR_INVALID_ARG;
+  int msp;
+  losa_status s = check_kv(ctx, kv, false, &msp);
+  if (s != LOSA_OK) return s;
+  if (!q || !o_p || !lse_p) return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_sparse_attn: NULL pointer");
+  if ((active_idx == nullptr) != (active_count == nullptr))
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "active_idx and active_count must both be given or both be NULL");
+  if ((sel_pages == nullptr) != (sel_count == nullptr))
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "sel_pages and sel_count must both be given or both be NULL");
+  if (sel_pages && cap < 1) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap must be >= 1");
+  return sparse_attn_impl(ctx, as_stream(stream), view_of(kv), kv->batch, msp, q, active_idx, active_count, sel_pages,
+                          sel_count, cap, (float*)o_p, lse_p);
+}
+
+losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t step_index, const void* h_cur,
+                      const void* h_prev, const void* q, losa_select_mode mode, float param, int32_t topk_pages,
+                      void* o_p, float* lse_p, uint8_t* mask, int32_t* sel_count) {
+  if (!ctx) return LOSA_ERR_INVALID_ARG;
+  int msp;
+  const bool dense = step_index == 0;
+  losa_status s = check_kv(ctx, kv, !dense, &msp);
+  if (s != LOSA_OK) return s;
+  if (step_index < 0) return fail(ctx, LOSA_ERR_INVALID_ARG, "step_index is negative");
+  if (!q || !o_p || !lse_p) return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_step: NULL pointer");
+  hipStream_t st = as_stream(stream);
+  const KvView view = view_of(kv);
+  if (dense)
+    return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, nullptr, nullptr, nullptr, nullptr, 0, (float*)o_p, lse_p);
+  if (!h_cur || !h_prev) return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_step: h_cur / h_prev are NULL");
+  if (topk_pages < 1 || topk_pages > ctx->cfg.max_topk_pages)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "topk_pages %d outside 1..max_topk_pages (%d)", topk_pages,
+                ctx->cfg.max_topk_pages);
+  uint8_t* mk = mask ? mask : ctx->mask;
+  int32_t* sc = sel_count ? sel_count : ctx->sel_count;
+  s = select_active_impl(ctx, st, kv->batch, h_cur, h_prev, (int)mode, param, ctx->delta, mk, ctx->active_idx,
+                         ctx->active_count);
+  if (s != LOSA_OK) return s;
+  const int cap = ctx->sh.max_pages;
+  s = score_pages_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, topk_pages, nullptr,
+                       ctx->sel_pages, sc, cap);
+  if (s != LOSA_OK) return s;
+  return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, ctx->sel_pages, sc,
+                          cap, (float*)o_p, lse_p);
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Internal declarations shared by the translation units of liblosa.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "losa.h"
+
+namespace losa {
+
+constexpr int kWave = 64;
+
+// Device view of the ragged page table, passed to kernels by value.
+struct KvView {
+  const void* k_pages;
+  const void* v_pages;
+  void* meta;
+  const int32_t* page_indptr;
+  const int32_t* page_indices;
+  const int32_t* seq_lens;
+  int32_t num_pages;
+};
+
+// Static problem shape, passed to kernels by value.
+struct Shape {
+  int32_t Hq, Hkv, G, d, H, g, B;
+  int32_t max_pages;   // row stride of the score matrix / bitmap sizing (config.max_pages_per_seq)
+  int32_t rows_max;    // B * G: rows of one KV head when every token is active
+  float sm_scale;
+};
+
+// Split-K partials of the attention: item = ((b*Hkv + j)*nchunk + c), row r < rows_max.
+struct Partials {
+  float* o;   // [items, rows_max, d]   un-normalised sum_t exp(s_t - m) v_t
+  float* m;   // [items, rows_max]      running max of the scaled scores
+  float* l;   // [items, rows_max]      sum_t exp(s_t - m)
+};
+
+// ---- select_active.hip
+hipError_t launch_locality_delta(hipStream_t st, int dtype, const void* h_cur, const void* h_prev,
+                                 int rows, int H, float* delta);
+hipError_t launch_rank_select(hipStream_t st, const float* delta, int batch, int B, int mode, int n, float tau,
+                              uint8_t* mask, int32_t* active_idx, int32_t* active_count);
+
+// ---- page_bounds.hip
+hipError_t launch_page_bounds(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
+                              int first_page, int num_pages_in_range);
+
+// ---- score_pages.hip
+hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
+                              const void* q, const int32_t* active_idx, const int32_t* active_count,
+                              float* scores, uint32_t* bitmap);
+hipError_t launch_topk_union(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
+                             const int32_t* active_count, const float* scores, int topk, int32_t* topk_out,
+                             uint32_t* bitmap);
+hipError_t launch_union_compact(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
+                                const int32_t* active_count, const uint32_t* bitmap,
+                                int32_t* sel_pages, int32_t* sel_count, int cap);
+
+// ---- sparse_attn.hip
+hipError_t launch_attn_partials(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
+                                const void* q, const int32_t* active_idx, const int32_t* active_count,
+                                const int32_t* sel_pages, const int32_t* sel_count, int cap,
+                                int chunk_pages, int nchunk, const Partials& part);
+hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch,
+                             const int32_t* active_idx, const int32_t* active_count,
+                             const int32_t* sel_count, int cap, int chunk_pages, int nchunk, bool log2_units,
+                             const Partials& part, float* o_p, float* lse_p);
+
+}  // namespace losa

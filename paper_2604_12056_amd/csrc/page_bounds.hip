@@ -1,0 +1,90 @@
+// QUEST page metadata (paper: Preliminaries, Sparse Attention Algorithms for LLMs): the
+// elementwise min key and max key of every page, per KV head.
+//
+// Pure streaming: a (page, head) key tile is g*d contiguous elements; d*sizeof(T)/16 lanes
+// each walk one 16-byte column strip down the g token rows with all loads issued up front,
+// so a wavefront keeps several KiB in flight.  Compare-only arithmetic: the outputs are
+// values of the page, exact in the storage type.
+#include "losa_device.h"
+#include "losa_internal.h"
+
+namespace losa {
+
+__device__ __forceinline__ uint4 pack16(const float (&f)[8], bf16_t) {
+  uint4 r;
+  r.x = (__float_as_uint(f[0]) >> 16) | (__float_as_uint(f[1]) & 0xFFFF0000u);
+  r.y = (__float_as_uint(f[2]) >> 16) | (__float_as_uint(f[3]) & 0xFFFF0000u);
+  r.z = (__float_as_uint(f[4]) >> 16) | (__float_as_uint(f[5]) & 0xFFFF0000u);
+  r.w = (__float_as_uint(f[6]) >> 16) | (__float_as_uint(f[7]) & 0xFFFF0000u);
+  return r;
+}
+__device__ __forceinline__ uint4 pack16(const float (&f)[4], float) {
+  return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+}
+
+template <typename T, int D, int GP>
+__global__ __launch_bounds__(256) void page_bounds_kernel(KvView kv, int Hkv, int first_page, int npages_range) {
+  constexpr int V = Vec16<T>::n;
+  constexpr int TPT = D / V;        // lanes per (page, head) tile
+  constexpr int TILES = 256 / TPT;  // tiles per workgroup
+  const int b = blockIdx.y;
+  const int tile = blockIdx.x * TILES + threadIdx.x / TPT;
+  const int lane = threadIdx.x % TPT;
+  const int p_rel = tile / Hkv, j = tile % Hkv;
+  if (p_rel >= npages_range) return;
+  const int p = first_page + p_rel;
+  const int base = kv.page_indptr[b];
+  if (p >= kv.page_indptr[b + 1] - base) return;
+  const int phys = kv.page_indices[base + p];
+  if ((unsigned)phys >= (unsigned)kv.num_pages) return;
+  const int valid = min(GP, kv.seq_lens[b] - p * GP);
+  if (valid <= 0) return;
+
+  const size_t tile_id = (size_t)phys * Hkv + j;
+  const uint4* src = reinterpret_cast<const uint4*>((const T*)kv.k_pages + tile_id * GP * D) + lane;
+  uint4 raw[GP];
+#pragma unroll
+  for (int t = 0; t < GP; ++t) raw[t] = src[t * TPT];
+  float mn[V], mx[V];
+  widen16(raw[0], mn, T());
+#pragma unroll
+  for (int e = 0; e < V; ++e) mx[e] = mn[e];
+#pragma unroll
+  for (int t = 1; t < GP; ++t) {
+    float f[V];
+    widen16(raw[t], f, T());
+    const bool ok = t < valid;
+#pragma unroll
+    for (int e = 0; e < V; ++e) {
+      mn[e] = ok ? fminf(mn[e], f[e]) : mn[e];
+      mx[e] = ok ? fmaxf(mx[e], f[e]) : mx[e];
+    }
+  }
+  uint4* dst = reinterpret_cast<uint4*>((T*)kv.meta + tile_id * 2 * D) + lane;
+  dst[0] = pack16(mn, T());
+  dst[TPT] = pack16(mx, T());
+}
+
+template <typename T, int D>
+static hipError_t launch_g(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int first_page, int n) {
+  constexpr int TILES = 256 / (D / Vec16<T>::n);
+  const long tiles = (long)n * sh.Hkv;
+  dim3 grid((unsigned)((tiles + TILES - 1) / TILES), batch);
+  if (sh.g == 16)
+    page_bounds_kernel<T, D, 16><<<grid, 256, 0, st>>>(kv, sh.Hkv, first_page, n);
+  else
+    page_bounds_kernel<T, D, 32><<<grid, 256, 0, st>>>(kv, sh.Hkv, first_page, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_page_bounds(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch, int first_page,
+                              int n) {
+  if (n <= 0 || batch <= 0) return hipSuccess;
+  if (dtype == LOSA_BF16)
+    return sh.d == 128 ? launch_g<bf16_t, 128>(st, kv, sh, batch, first_page, n)
+                       : launch_g<bf16_t, 64>(st, kv, sh, batch, first_page, n);
+  return sh.d == 128 ? launch_g<float, 128>(st, kv, sh, batch, first_page, n)
+                     : launch_g<float, 64>(st, kv, sh, batch, first_page, n);
+}
+
+}  // namespace losa

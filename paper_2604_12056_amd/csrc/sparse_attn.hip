@@ -1,0 +1,268 @@
+// Paged sparse prefix attention for the active queries, split over page chunks
+// (paper: Preliminaries, Attention Decomposition With Online Softmax; Methodology, eq. update_rule).
+//
+// Work item = (sequence b, KV head j, block of query rows, chunk of the KV head's page list).
+// Each item keeps a running (max, sum, un-normalised output) per row and writes it as a
+// partial; attn_merge combines the chunks of a row in chunk order with the same
+// log-sum-exp rule the paper uses to merge prefix and block parts, normalises, and writes
+// (o_p, lse_p) at the active token's row.  No float atomics anywhere: results do not
+// depend on scheduling.
+//
+// This file holds the element-type-generic kernel (vector ALUs, K/V tiles staged in LDS as
+// float); it serves the float mode and is the fallback shape for bfloat16.
+#include <math.h>
+
+#include "losa_device.h"
+#include "losa_internal.h"
+
+namespace losa {
+
+constexpr int kRowBlock = 32;  // query rows per work item (generic kernel)
+constexpr int kTileTok = 32;   // tokens per LDS tile
+
+template <typename T, int D, int GP>
+__global__ __launch_bounds__(256) void attn_partials_generic_kernel(
+    KvView kv, Shape sh, const T* __restrict__ q, const int32_t* __restrict__ active_idx,
+    const int32_t* __restrict__ active_count, const int32_t* __restrict__ sel_pages,
+    const int32_t* __restrict__ sel_count, int cap, int chunk_pages, int nchunk, int nrb, Partials part) {
+  constexpr int V = Vec16<T>::n;
+  constexpr int VPR = D / V;           // 16-byte vectors per key row
+  constexpr int PPT = kTileTok / GP;   // pages per tile
+  constexpr int VPC = GP / V;          // 16-byte vectors per value channel row of a page
+  constexpr int CPT = D / 8;           // output channels per thread
+  __shared__ float qs[kRowBlock][D + 1];
+  __shared__ float ks[kTileTok][D + 1];
+  __shared__ float vs[kTileTok][D + 1];
+  __shared__ float ps[kRowBlock][kTileTok + 1];
+  __shared__ int tok_ok[kTileTok];
+
+  const int chunk = blockIdx.x, j = blockIdx.y / nrb, rb = blockIdx.y % nrb, b = blockIdx.z, tid = threadIdx.x;
+  const int n = active_idx ? min(active_count[b], sh.B) : sh.B;
+  const int M = n * sh.G, r0 = rb * kRowBlock;
+  if (r0 >= M) return;
+  const int base = kv.page_indptr[b];
+  const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
+  const int L = kv.seq_lens[b];
+  const int32_t* list = sel_pages ? sel_pages + ((size_t)b * sh.Hkv + j) * cap : nullptr;
+  const int U = list ? min(sel_count[b * sh.Hkv + j], cap) : P;
+  const int c0 = chunk * chunk_pages;
+  if (c0 >= U) return;
+  const int c1 = min(U, c0 + chunk_pages);
+
+  for (int v = tid; v < kRowBlock * VPR; v += 256) {
+    const int rr = v / VPR, cv = v % VPR, r = r0 + rr;
+    float f[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) f[e] = 0.f;
+    if (r < M) {
+      const int a = r / sh.G, hg = r % sh.G;
+      const int tok = active_idx ? active_idx[(size_t)b * sh.B + a] : a;
+      if ((unsigned)tok < (unsigned)sh.B) {
+        const uint4 raw = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + hg) * D)[cv];
+        widen16(raw, f, T());
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < V; ++e) qs[rr][cv * V + e] = f[e];
+  }
+
+  const int row = tid / 8, sub = tid % 8;
+  float m = -INFINITY, l = 0.f, acc[CPT];
+#pragma unroll
+  for (int k = 0; k < CPT; ++k) acc[k] = 0.f;
+
+  for (int pp = c0; pp < c1; pp += PPT) {
+    __syncthreads();
+    // ---- stage one tile of keys (token-major pages) and values (channel-major pages)
+    for (int v = tid; v < kTileTok * VPR; v += 256) {
+      const int ts = v / VPR, cv = v % VPR;
+      const int lp = pp + ts / GP, tin = ts % GP;
+      float f[V];
+#pragma unroll
+      for (int e = 0; e < V; ++e) f[e] = 0.f;
+      int ok = 0;
+      if (lp < c1) {
+        const int logical = list ? list[lp] : lp;
+        if ((unsigned)logical < (unsigned)P && logical * GP + tin < L) {
+          const int phys = kv.page_indices[base + logical];
+          if ((unsigned)phys < (unsigned)kv.num_pages) {
+            ok = 1;
+            const uint4 raw = reinterpret_cast<const uint4*>((const T*)kv.k_pages + (((size_t)phys * sh.Hkv + j) * GP + tin) * D)[cv];
+            widen16(raw, f, T());
+          }
+        }
+      }
+      if (cv == 0) tok_ok[ts] = ok;
+#pragma unroll
+      for (int e = 0; e < V; ++e) ks[ts][cv * V + e] = f[e];
+    }
+    for (int v = tid; v < PPT * D * VPC; v += 256) {
+      const int pgi = v / (D * VPC), rem = v % (D * VPC), c = rem / VPC, tv = rem % VPC;
+      const int lp = pp + pgi;
+      float f[V];
+#pragma unroll
+      for (int e = 0; e < V; ++e) f[e] = 0.f;
+      int logical = -1;
+      if (lp < c1) {
+        logical = list ? list[lp] : lp;
+        if ((unsigned)logical < (unsigned)P) {
+          const int phys = kv.page_indices[base + logical];
+          if ((unsigned)phys < (unsigned)kv.num_pages) {
+            const uint4 raw = reinterpret_cast<const uint4*>((const T*)kv.v_pages + (((size_t)phys * sh.Hkv + j) * D + c) * GP)[tv];
+            widen16(raw, f, T());
+          } else {
+            logical = -1;
+          }
+        } else {
+          logical = -1;
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        const int tin = tv * V + e;
+        const bool ok = logical >= 0 && logical * GP + tin < L;
+        vs[pgi * GP + tin][c] = ok ? f[e] : 0.f;   // slots past the sequence end may hold NaN
+      }
+    }
+    __syncthreads();
+    // ---- scores of this thread's row against 4 tokens
+    float s[4], tmax = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int ts = sub + 8 * k;
+      float dot = 0.f;
+#pragma unroll 8
+      for (int c = 0; c < D; ++c) dot = fmaf(qs[row][c], ks[ts][c], dot);
+      s[k] = tok_ok[ts] ? dot * sh.sm_scale : -INFINITY;
+      tmax = fmaxf(tmax, s[k]);
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 1, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 2, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 4, 64));
+    const float m_new = fmaxf(m, tmax);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = expf(m - m_use);
+    float psum = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float p = expf(s[k] - m_use);
+      ps[row][sub + 8 * k] = p;
+      psum += p;
+    }
+    psum += __shfl_xor(psum, 1, 64);
+    psum += __shfl_xor(psum, 2, 64);
+    psum += __shfl_xor(psum, 4, 64);
+    l = l * alpha + psum;
+    m = m_new;
+    __syncthreads();
+    // ---- output channels sub, sub+8, ... of this thread's row
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) {
+      float a = acc[k] * alpha;
+#pragma unroll 8
+      for (int ts = 0; ts < kTileTok; ++ts) a = fmaf(ps[row][ts], vs[ts][sub + 8 * k], a);
+      acc[k] = a;
+    }
+  }
+  const int r = r0 + row;
+  if (r < M) {
+    const size_t item = ((size_t)b * sh.Hkv + j) * nchunk + chunk;
+    const size_t prow = item * sh.rows_max + r;
+#pragma unroll
+    for (int k = 0; k < CPT; ++k) part.o[prow * D + sub + 8 * k] = acc[k];
+    if (sub == 0) {
+      part.m[prow] = m;
+      part.l[prow] = l;
+    }
+  }
+}
+
+// Combine the chunk partials of one query row.  LOG2: partial maxima are in log2 units
+// (scores were scaled by sm_scale*log2(e)); otherwise natural units.
+template <int D, bool LOG2>
+__global__ __launch_bounds__(D) void attn_merge_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_idx,
+                                                       const int32_t* __restrict__ active_count,
+                                                       const int32_t* __restrict__ sel_count, int cap, int chunk_pages,
+                                                       int nchunk, Partials part, float* __restrict__ o_p,
+                                                       float* __restrict__ lse_p) {
+  const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, ch = threadIdx.x;
+  const int n = active_idx ? min(active_count[b], sh.B) : sh.B;
+  if (r >= n * sh.G) return;
+  const int a = r / sh.G, hg = r % sh.G;
+  const int tok = active_idx ? active_idx[(size_t)b * sh.B + a] : a;
+  if ((unsigned)tok >= (unsigned)sh.B) return;
+  const int P = min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages);
+  const int U = sel_count ? min(sel_count[b * sh.Hkv + j], cap) : P;
+  const int live = min(nchunk, (U + chunk_pages - 1) / chunk_pages);
+  const size_t item0 = ((size_t)b * sh.Hkv + j) * nchunk;
+  float m_tot = -INFINITY;
+  for (int c = 0; c < live; ++c) m_tot = fmaxf(m_tot, part.m[(item0 + c) * sh.rows_max + r]);
+  const size_t orow = ((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + hg;
+  if (m_tot == -INFINITY) {   // no valid token at all
+    o_p[orow * D + ch] = 0.f;
+    if (ch == 0) lse_p[orow] = -INFINITY;
+    return;
+  }
+  float l = 0.f, o = 0.f;
+  for (int c = 0; c < live; ++c) {
+    const size_t prow = (item0 + c) * sh.rows_max + r;
+    const float dm = part.m[prow] - m_tot;
+    const float w = LOG2 ? exp2f(dm) : expf(dm);
+    l = fmaf(part.l[prow], w, l);
+    o = fmaf(part.o[prow * D + ch], w, o);
+  }
+  o_p[orow * D + ch] = o / l;
+  if (ch == 0) lse_p[orow] = LOG2 ? (m_tot + log2f(l)) * 0.6931471805599453f : m_tot + logf(l);
+}
+
+template <typename T, int D>
+static hipError_t launch_generic(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
+                                 const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
+                                 const int32_t* sel_count, int cap, int chunk_pages, int nchunk,
+                                 const Partials& part) {
+  const int nrb = (sh.rows_max + kRowBlock - 1) / kRowBlock;
+  dim3 grid(nchunk, sh.Hkv * nrb, batch);
+  if (sh.g == 16)
+    attn_partials_generic_kernel<T, D, 16><<<grid, 256, 0, st>>>(kv, sh, (const T*)q, active_idx, active_count,
+                                                                 sel_pages, sel_count, cap, chunk_pages, nchunk, nrb, part);
+  else
+    attn_partials_generic_kernel<T, D, 32><<<grid, 256, 0, st>>>(kv, sh, (const T*)q, active_idx, active_count,
+                                                                 sel_pages, sel_count, cap, chunk_pages, nchunk, nrb, part);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_partials(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch, const void* q,
+                                const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
+                                const int32_t* sel_count, int cap, int chunk_pages, int nchunk, const Partials& part) {
+  if (batch <= 0 || nchunk <= 0) return hipSuccess;
+  if (dtype == LOSA_BF16)
+    return sh.d == 128 ? launch_generic<bf16_t, 128>(st, kv, sh, batch, q, active_idx, active_count, sel_pages,
+                                                     sel_count, cap, chunk_pages, nchunk, part)
+                       : launch_generic<bf16_t, 64>(st, kv, sh, batch, q, active_idx, active_count, sel_pages,
+                                                    sel_count, cap, chunk_pages, nchunk, part);
+  return sh.d == 128 ? launch_generic<float, 128>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count,
+                                                  cap, chunk_pages, nchunk, part)
+                     : launch_generic<float, 64>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count,
+                                                 cap, chunk_pages, nchunk, part);
+}
+
+hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const int32_t* active_idx,
+                             const int32_t* active_count, const int32_t* sel_count, int cap, int chunk_pages,
+                             int nchunk, bool log2_units, const Partials& part, float* o_p, float* lse_p) {
+  if (batch <= 0) return hipSuccess;
+  dim3 grid(sh.rows_max, sh.Hkv, batch);
+  if (sh.d == 128) {
+    if (log2_units)
+      attn_merge_kernel<128, true><<<grid, 128, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, chunk_pages, nchunk, part, o_p, lse_p);
+    else
+      attn_merge_kernel<128, false><<<grid, 128, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, chunk_pages, nchunk, part, o_p, lse_p);
+  } else {
+    if (log2_units)
+      attn_merge_kernel<64, true><<<grid, 64, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, chunk_pages, nchunk, part, o_p, lse_p);
+    else
+      attn_merge_kernel<64, false><<<grid, 64, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, chunk_pages, nchunk, part, o_p, lse_p);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace losa

@@ -1,0 +1,135 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element,
+on seeded inputs that span several tiles and a ragged tail; then losa_step end to end."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import losa_oracle as orc
+from paper_2604_12056_amd import binding as L
+from paper_2604_12056_amd import synth
+
+from parity_util import (Rig, check_page_bounds, check_score_pages, check_select_active, check_sparse_attn,
+                         compare_state, run_steps_end_to_end, upload_active, upload_union)
+
+pytestmark = pytest.mark.gpu
+
+
+def small_workloads():
+    c0 = synth.config(0)
+    c1 = synth.config(1).replace(seq_lens=(3000,), topk_pages=16, T=4)                      # 187.5 pages: ragged tail
+    c2 = synth.config(2).replace(batch=3, seq_lens=(1000, 517, 2049), topk_pages=8, T=4)      # ragged batch
+    c3 = synth.config(3).replace(seq_lens=(6000,), topk_pages=24, T=3)
+    c4 = synth.config(4).replace(batch=2, seq_lens=(4096 + 5, 2048), topk_pages=8, T=3)       # g=32, B=64
+    c4all = c4.replace(n_active=64, seq_lens=(1024 + 7, 640), topk_pages=4, name="C4-all-active")
+    f0 = synth.config(0, dtype="f32").replace(name="C0-f32")
+    f1 = synth.config(1, dtype="f32").replace(seq_lens=(1500,), topk_pages=8, T=3, name="C1-f32")
+    return [c0, c1, c2, c3, c4, c4all, f0, f1]
+
+
+@pytest.fixture(scope="module", params=small_workloads(), ids=lambda w: w.name)
+def rig(request):
+    r = Rig(request.param)
+    yield r
+    r.close()
+
+
+def test_page_bounds(rig):
+    check_page_bounds(rig)
+
+
+def test_select_active_all_modes(rig):
+    w = rig.w
+    for t in range(1, w.T):
+        A = check_select_active(rig, t, orc.SEL_TOPK, float(w.n_active))
+        for b in range(w.batch):
+            assert np.array_equal(A[b], rig.inp.picked[t, b])
+    check_select_active(rig, 1, orc.SEL_FRACTION, w.n_active / w.B)
+    check_select_active(rig, 1, orc.SEL_FRACTION, 1.0)
+    check_select_active(rig, 1, orc.SEL_THRESHOLD, 0.01)
+    check_select_active(rig, 1, orc.SEL_THRESHOLD, 1e9)        # empty active set
+    check_select_active(rig, 1, orc.SEL_TOPK, 0.0)
+    assert rig.near_ties == 0
+
+
+def test_score_pages_and_union(rig):
+    w = rig.w
+    check_page_bounds(rig)
+    active = [rig.inp.picked[1, b] for b in range(w.batch)]
+    check_score_pages(rig, 1, active, w.topk_pages)
+    check_score_pages(rig, 2, [np.arange(w.B, dtype=np.int32)] * w.batch, max(1, w.topk_pages // 2))   # all tokens
+    check_score_pages(rig, 1, active, 1)
+    assert rig.near_ties <= 2
+
+
+def test_sparse_attn_dense_then_sparse(rig):
+    w = rig.w
+    check_page_bounds(rig)
+    check_sparse_attn(rig, 0, None, None, dense=True)
+    active = [rig.inp.picked[1, b] for b in range(w.batch)]
+    _, _, union = __import__("parity_util").oracle_selection(rig, 1, active, w.topk_pages)
+    check_sparse_attn(rig, 1, active, union)
+    # a single page per KV head, and the last (possibly partial) page only
+    one = {(b, j): np.array([w.pages_per_seq[b] - 1], dtype=np.int32) for b in range(w.batch) for j in range(w.Hkv)}
+    check_sparse_attn(rig, 2, active, one)
+
+
+def test_losa_step_end_to_end(rig):
+    w = rig.w
+    check_page_bounds(rig)
+    run_steps_end_to_end(rig, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+    assert rig.near_ties <= 2
+
+
+def test_budget_covering_every_page_equals_dense(rig):
+    """All tokens active and K >= P: the sparse path must reproduce dense prefix attention."""
+    w, blk = rig.w, rig.blk
+    check_page_bounds(rig)
+    if w.max_pages > rig.ctx.cfg.max_topk_pages:
+        pytest.skip("budget below the page count for this workload")
+    L.losa_step(rig.ctx, rig.layer.kv, 1, blk.h[1], blk.h[0], blk.q[1], orc.SEL_FRACTION, 1.0,
+                rig.ctx.cfg.max_topk_pages, blk.o_p, blk.lse_p)
+    torch.cuda.synchronize()
+    orc.losa_step(rig.cache, 0, None, None, rig.inp.q[1], 0, 0, 0, w.B, w.Hq, rig.o_ref, rig.L_ref)
+    compare_state(rig, [np.arange(w.B)] * w.batch)
+
+
+def test_run_twice_is_bitwise_identical(rig):
+    w, blk = rig.w, rig.blk
+    check_page_bounds(rig)
+    outs = []
+    for _ in range(2):
+        blk.o_p.zero_(); blk.lse_p.zero_()
+        for t in range(min(3, w.T)):
+            L.losa_step(rig.ctx, rig.layer.kv, t, blk.h[t] if t else None, blk.h[t - 1] if t else None, blk.q[t],
+                        orc.SEL_TOPK, float(w.n_active), w.topk_pages, blk.o_p, blk.lse_p)
+        torch.cuda.synchronize()
+        outs.append((blk.o_p.clone(), blk.lse_p.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
+# ------------------------------------------------------------------ degenerate shapes
+@pytest.mark.parametrize("seq_lens", [(1,), (15,), (16,), (17, 1, 33)])
+def test_tiny_prefixes(seq_lens):
+    w = synth.config(0).replace(batch=len(seq_lens), seq_lens=tuple(seq_lens), topk_pages=2, T=3, n_active=3)
+    rig = Rig(w)
+    try:
+        check_page_bounds(rig)
+        run_steps_end_to_end(rig, range(w.T), orc.SEL_TOPK, 3.0, 2)
+    finally:
+        rig.close()
+
+
+def test_empty_active_set_is_a_no_op():
+    w = synth.config(0).replace(T=2)
+    rig = Rig(w)
+    try:
+        blk = rig.blk
+        check_page_bounds(rig)
+        blk.o_p.fill_(3.0); blk.lse_p.fill_(-1.0)
+        L.losa_step(rig.ctx, rig.layer.kv, 1, blk.h[1], blk.h[0], blk.q[1], orc.SEL_THRESHOLD, 1e9, 4,
+                    blk.o_p, blk.lse_p, blk.mask, blk.sel_count)
+        torch.cuda.synchronize()
+        assert bool((blk.o_p == 3.0).all()) and bool((blk.lse_p == -1.0).all())
+        assert int(blk.mask.sum()) == 0 and int(blk.sel_count.sum()) == 0
+    finally:
+        rig.close()
