@@ -20,6 +20,14 @@ namespace losa {
 constexpr int kRowBlock = 32;  // query rows per work item (generic kernel)
 constexpr int kTileTok = 32;   // tokens per LDS tile
 
+// Accumulation type of the generic kernel.  bfloat16 inputs: float (products are exact, the
+// 2e-2 bound is far away).  float inputs: double, because the float mode's 1e-4 bound is
+// within reach of float summation error once outlier channels push |q.k| into the hundreds.
+template <typename T> struct AccOf { typedef float type; };
+template <> struct AccOf<float> { typedef double type; };
+__device__ __forceinline__ float exp_acc(float x) { return expf(x); }
+__device__ __forceinline__ double exp_acc(double x) { return exp(x); }
+
 template <typename T, int D, int GP>
 __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
     KvView kv, Shape sh, const T* __restrict__ q, const int32_t* __restrict__ active_idx,
@@ -33,7 +41,7 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
   __shared__ float qs[kRowBlock][D + 1];
   __shared__ float ks[kTileTok][D + 1];
   __shared__ float vs[kTileTok][D + 1];
-  __shared__ float ps[kRowBlock][kTileTok + 1];
+  __shared__ typename AccOf<T>::type ps[kRowBlock][kTileTok + 1];
   __shared__ int tok_ok[kTileTok];
 
   const int chunk = blockIdx.x, j = blockIdx.y / nrb, rb = blockIdx.y % nrb, b = blockIdx.z, tid = threadIdx.x;
@@ -66,10 +74,12 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
     for (int e = 0; e < V; ++e) qs[rr][cv * V + e] = f[e];
   }
 
+  typedef typename AccOf<T>::type Acc;
   const int row = tid / 8, sub = tid % 8;
-  float m = -INFINITY, l = 0.f, acc[CPT];
+  float m = -INFINITY;   // running reference point of the exponentials (any value near the max works)
+  Acc l = 0, acc[CPT];
 #pragma unroll
-  for (int k = 0; k < CPT; ++k) acc[k] = 0.f;
+  for (int k = 0; k < CPT; ++k) acc[k] = 0;
 
   for (int pp = c0; pp < c1; pp += PPT) {
     __syncthreads();
@@ -126,26 +136,27 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
     }
     __syncthreads();
     // ---- scores of this thread's row against 4 tokens
-    float s[4], tmax = -INFINITY;
+    Acc s[4];
+    float tmax = -INFINITY;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       const int ts = sub + 8 * k;
-      float dot = 0.f;
+      Acc dot = 0;
 #pragma unroll 8
-      for (int c = 0; c < D; ++c) dot = fmaf(qs[row][c], ks[ts][c], dot);
-      s[k] = tok_ok[ts] ? dot * sh.sm_scale : -INFINITY;
-      tmax = fmaxf(tmax, s[k]);
+      for (int c = 0; c < D; ++c) dot += (Acc)qs[row][c] * (Acc)ks[ts][c];
+      s[k] = tok_ok[ts] ? dot * (Acc)sh.sm_scale : (Acc)-INFINITY;
+      tmax = fmaxf(tmax, (float)s[k]);
     }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 1, 64));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 2, 64));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 4, 64));
     const float m_new = fmaxf(m, tmax);
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = expf(m - m_use);
-    float psum = 0.f;
+    const Acc alpha = exp_acc((Acc)m - (Acc)m_use);
+    Acc psum = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const float p = expf(s[k] - m_use);
+      const Acc p = exp_acc(s[k] - (Acc)m_use);
       ps[row][sub + 8 * k] = p;
       psum += p;
     }
@@ -158,9 +169,9 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
     // ---- output channels sub, sub+8, ... of this thread's row
 #pragma unroll
     for (int k = 0; k < CPT; ++k) {
-      float a = acc[k] * alpha;
+      Acc a = acc[k] * alpha;
 #pragma unroll 8
-      for (int ts = 0; ts < kTileTok; ++ts) a = fmaf(ps[row][ts], vs[ts][sub + 8 * k], a);
+      for (int ts = 0; ts < kTileTok; ++ts) a += (Acc)ps[row][ts] * (Acc)vs[ts][sub + 8 * k];
       acc[k] = a;
     }
   }
@@ -169,10 +180,10 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
     const size_t item = ((size_t)b * sh.Hkv + j) * nchunk + chunk;
     const size_t prow = item * sh.rows_max + r;
 #pragma unroll
-    for (int k = 0; k < CPT; ++k) part.o[prow * D + sub + 8 * k] = acc[k];
+    for (int k = 0; k < CPT; ++k) part.o[prow * D + sub + 8 * k] = (float)acc[k];
     if (sub == 0) {
       part.m[prow] = m;
-      part.l[prow] = l;
+      part.l[prow] = (float)l;
     }
   }
 }
@@ -203,16 +214,27 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(KvView kv, Shape sh, cons
     if (ch == 0) lse_p[orow] = -INFINITY;
     return;
   }
-  float l = 0.f, o = 0.f;
-  for (int c = 0; c < live; ++c) {
-    const size_t prow = (item0 + c) * sh.rows_max + r;
-    const float dm = part.m[prow] - m_tot;
-    const float w = LOG2 ? exp2f(dm) : expf(dm);
-    l = fmaf(part.l[prow], w, l);
-    o = fmaf(part.o[prow * D + ch], w, o);
+  if (LOG2) {
+    float l = 0.f, o = 0.f;
+    for (int c = 0; c < live; ++c) {
+      const size_t prow = (item0 + c) * sh.rows_max + r;
+      const float w = exp2f(part.m[prow] - m_tot);
+      l = fmaf(part.l[prow], w, l);
+      o = fmaf(part.o[prow * D + ch], w, o);
+    }
+    o_p[orow * D + ch] = o / l;
+    if (ch == 0) lse_p[orow] = (m_tot + log2f(l)) * 0.6931471805599453f;
+  } else {   // natural units: the generic kernel, which also serves the float mode; combine in double
+    double l = 0., o = 0.;
+    for (int c = 0; c < live; ++c) {
+      const size_t prow = (item0 + c) * sh.rows_max + r;
+      const double w = exp((double)part.m[prow] - (double)m_tot);
+      l += (double)part.l[prow] * w;
+      o += (double)part.o[prow * D + ch] * w;
+    }
+    o_p[orow * D + ch] = (float)(o / l);
+    if (ch == 0) lse_p[orow] = (float)((double)m_tot + log(l));
   }
-  o_p[orow * D + ch] = o / l;
-  if (ch == 0) lse_p[orow] = LOG2 ? (m_tot + log2f(l)) * 0.6931471805599453f : m_tot + logf(l);
 }
 
 template <typename T, int D>
