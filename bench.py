@@ -1,0 +1,203 @@
+#!/usr/bin/env python3
+"""Benchmark of the LoSA prefix-attention hot path on one MI355X.
+
+A "step" is one sparse denoising step (step index >= 1) of ONE layer through losa_step:
+locality score + active set, page scoring + top-k + union, paged sparse attention of the
+active queries, stable rows reused.  The workload is benchmark configuration C1
+(Qwen2.5-7B-like layer, 32k-token prefix, block 32, 20 % active, 2048-token budget).
+Consecutive steps rotate over `--layers` independent KV caches (a model's layers), so
+every step reads its pages from HBM rather than from the 256 MiB last-level cache.
+
+Prints ONE JSON line.  `value` = microseconds per step per layer (lower is better), inputs
+resident in HBM.  `roofline` is for the dominant kernel (the split-K attention kernel):
+algorithmic bytes (K+V of the pages touched, active queries, partials written) divided by
+the kernel's mean duration from HIP events recorded on its stream in a second timed pass
+over the same steps.  `cpu_baseline` times the numpy oracle on a sample of the same steps.
+Also reported: dense initialisation (step 0) and page-bounds build times per layer.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=480)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--config", type=int, default=1, help="benchmark configuration index (default C1)")
+    ap.add_argument("--layers", type=int, default=16, help="independent KV caches rotated over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph replay")
+    ap.add_argument("--cpu-steps", type=int, default=12, help="oracle steps timed for cpu_baseline")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only; run with --gpus 1 (no multi-GPU path exists)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2604_12056_amd import binding as L
+    from paper_2604_12056_amd import synth
+    from paper_2604_12056_amd.device_inputs import DeviceBlock, DeviceLayer, config_of
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = synth.config(args.config)
+    NL, T = args.layers, w.T
+    t0 = time.time()
+    inp0 = synth.make_inputs(w)
+    layers = [DeviceLayer(inp0, dev)]
+    for ell in range(1, NL):
+        wl = w.replace(seed=w.seed + 7919 * ell)
+        K, V = synth.make_kv(wl)
+        layers.append(DeviceLayer(synth.Inputs(wl, K, V, inp0.h, inp0.q, inp0.picked, inp0.seq_lens,
+                                               inp0.page_indptr, inp0.page_indices, inp0.num_pages), dev))
+    blocks = [DeviceBlock(inp0, dev) for _ in range(NL)]     # per-layer cached (o_p, lse_p)
+    ctx = L.losa_create(config_of(w), dev)
+    print(f"[bench] {w.name}: {NL} layers generated and uploaded in {time.time() - t0:.1f}s", file=sys.stderr, flush=True)
+
+    h, q = blocks[0].h, blocks[0].q
+    mode, param, topk = L.LOSA_SEL_TOPK, float(w.n_active), w.topk_pages
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    # ---- once per block: page bounds, then the dense initialisation (step 0) of every layer
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for ell in range(NL):
+        L.losa_page_bounds(ctx, layers[ell].kv)
+    e1.record()
+    torch.cuda.synchronize()
+    bounds_us = e0.elapsed_time(e1) * 1e3 / NL
+    for rep in range(2):
+        e0, e1 = ev(), ev()
+        e0.record()
+        for ell in range(NL):
+            L.losa_step(ctx, layers[ell].kv, 0, None, None, q[0], mode, param, topk, blocks[ell].o_p, blocks[ell].lse_p)
+        e1.record()
+        torch.cuda.synchronize()
+    dense_us = e0.elapsed_time(e1) * 1e3 / NL
+
+    # ---- the timed sparse steps
+    sel_counts = torch.zeros((args.steps, w.batch, w.Hkv), dtype=torch.int32, device=dev)
+
+    def run_steps(n, first, record=False):
+        for i in range(first, first + n):
+            ell = i % NL
+            t = 1 + (i // NL) % (T - 1)
+            L.losa_step(ctx, layers[ell].kv, t, h[t], h[t - 1], q[t], mode, param, topk,
+                        blocks[ell].o_p, blocks[ell].lse_p, None, sel_counts[i - first] if record else None)
+
+    run_steps(args.warmup, 0)
+    torch.cuda.synchronize()
+    # eager launches (one ctypes call per step): host-side launch cost included
+    e0, e1 = ev(), ev()
+    e0.record()
+    run_steps(args.steps, args.warmup)
+    e1.record()
+    torch.cuda.synchronize()
+    eager_us = e0.elapsed_time(e1) * 1e3 / args.steps
+    # the same K steps captured once into a HIP graph and replayed: the timed region
+    if args.no_graph:
+        total_ms, launch = eager_us * args.steps / 1e3, "eager"
+    else:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run_steps(args.steps, args.warmup)
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        total_ms, launch = e0.elapsed_time(e1), "hipGraph replay"
+    us_per_step = total_ms * 1e3 / args.steps
+
+    # ---- second pass over the same steps with per-kernel events on the launch stream
+    L.losa_profile_enable(ctx, True)
+    run_steps(args.steps, args.warmup, record=True)
+    torch.cuda.synchronize()
+    ms, cnt = L.losa_profile_read(ctx)
+    L.losa_profile_enable(ctx, False)
+    stage_us = {k: (ms[k] * 1e3 / cnt[k] if cnt[k] else None) for k in ms}
+
+    # ---- algorithmic bytes of the attention kernel per launch
+    e = 2 if w.dtype == "bf16" else 4
+    U = sel_counts.cpu().numpy().astype(np.float64)                    # [steps, batch, Hkv] pages
+    pages_per_launch = U.sum(axis=(1, 2)).mean()
+    rows = w.batch * w.n_active * w.Hq
+    kv_bytes = pages_per_launch * w.g * w.d * 2 * e
+    q_bytes = rows * w.d * e
+    attn_bytes = kv_bytes + q_bytes                                     # partials are overhead, not counted
+    attn_us = stage_us["attn"]
+    achieved = attn_bytes / (attn_us * 1e-6) / 1e9
+    meta_bytes = sum(w.pages_per_seq) * w.Hkv * 2 * w.d * e
+    step_bytes = attn_bytes + meta_bytes + 2 * w.batch * w.B * w.H * e + rows * (w.d + 1) * 4
+    density = pages_per_launch / (sum(w.pages_per_seq) * w.Hkv)
+
+    out = {
+        "metric": "sparse-attn us per denoise step per layer (32k prefix)" if args.config == 1
+        else "sparse-attn us per denoise step per layer",
+        "value": round(us_per_step, 3), "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(total_ms / args.steps, 6), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "q_heads": w.Hq, "kv_heads": w.Hkv, "head_dim": w.d,
+                   "prefix_tokens": list(w.seq_lens), "page_size": w.g, "block": w.B, "active_tokens": w.n_active,
+                   "budget_pages_per_query": w.topk_pages, "layers_rotated": NL, "denoise_steps": T,
+                   "step_kind": "sparse (step index >= 1), full losa_step", "launch": launch},
+        "eager_us_per_step": round(eager_us, 3),
+        "step_hbm_GBps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
+        "step_bytes": int(step_bytes),
+        "union_pages_per_kv_head": round(pages_per_launch / (w.batch * w.Hkv), 1),
+        "kv_density": round(float(density), 4),
+        "stage_us": {k: (round(v, 3) if v is not None else None) for k, v in stage_us.items()},
+        "dense_init_us_per_layer": round(dense_us, 2),
+        "dense_init_GBps": round(sum(w.seq_lens) * w.Hkv * w.d * 2 * e / (dense_us * 1e-6) / 1e9, 1),
+        "page_bounds_us_per_layer": round(bounds_us, 2),
+        "page_bounds_GBps": round((sum(w.seq_lens) * w.Hkv * w.d * e + meta_bytes) / (bounds_us * 1e-6) / 1e9, 1),
+        "roofline": {"kernel": "attn_partials (split-K sparse paged attention)", "bound": "hbm",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": int(attn_bytes), "us_per_launch": round(attn_us, 3)},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import losa_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        cache = orc.PrefixCache(inp0.K, inp0.V, w.g)       # page bounds are built once per block: not timed
+        o_ref = np.zeros((w.batch * w.B, w.Hq, w.d)); L_ref = np.zeros((w.batch * w.B, w.Hq))
+        n_cpu = min(args.cpu_steps, T - 1)
+        c0 = time.perf_counter()
+        for t in range(1, 1 + n_cpu):
+            orc.losa_step(cache, t, inp0.h[t], inp0.h[t - 1], inp0.q[t], mode, param, topk, w.B, w.Hq, o_ref, L_ref)
+        cpu_us = (time.perf_counter() - c0) * 1e6 / n_cpu
+        out["cpu_baseline"] = {"value": round(cpu_us, 1), "unit": "us", "cores": int(cores), "kind": "oracle",
+                               "sample": f"sparse steps 1..{n_cpu} of layer 0 of {w.name} (numpy float64 oracle)"}
+    ctx.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

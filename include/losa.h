@@ -164,6 +164,26 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
                       losa_select_mode mode, float param, int32_t topk_pages,
                       void* o_p, float* lse_p, uint8_t* mask, int32_t* sel_count);
 
+/* Measurement hooks (the paper's latency breakdown names four components: criticality
+ * estimation, locality pruning, cache management, attention computation; cache management
+ * costs nothing here because reuse is "do not write").  While enabled, every launch made
+ * through this context is bracketed by HIP events on its stream.
+ *   losa_profile_enable : enable != 0 creates the events (host objects), 0 releases them.
+ *   losa_profile_read   : waits for the recorded events, adds up the elapsed milliseconds and
+ *                         the launch count per stage into the two host arrays of
+ *                         LOSA_NUM_STAGES entries, and clears the record. */
+typedef enum {
+  LOSA_STAGE_LOCALITY = 0, /* locality score + ranking kernels        ("locality pruning") */
+  LOSA_STAGE_SCORE = 1,    /* page scoring kernel                      ("criticality estimation") */
+  LOSA_STAGE_TOPK = 2,     /* top-k + union kernels                    ("criticality estimation") */
+  LOSA_STAGE_ATTN = 3,     /* split-K attention kernel                 ("attention computation") */
+  LOSA_STAGE_MERGE = 4,    /* split-K merge kernel                     ("attention computation") */
+  LOSA_STAGE_BOUNDS = 5,   /* page min/max kernel (once per block) */
+  LOSA_NUM_STAGES = 6
+} losa_stage;
+losa_status losa_profile_enable(losa_ctx* ctx, int32_t enable);
+losa_status losa_profile_read(losa_ctx* ctx, double* stage_ms, int64_t* stage_launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,9 @@ LOSA_BF16, LOSA_F32 = 0, 1
 LOSA_SEL_TOPK, LOSA_SEL_FRACTION, LOSA_SEL_THRESHOLD = 0, 1, 2
 
 EXPORTS = ["losa_workspace_bytes", "losa_create", "losa_destroy", "losa_last_error", "losa_select_active",
-           "losa_page_bounds", "losa_score_pages", "losa_sparse_attn", "losa_step"]
+           "losa_page_bounds", "losa_score_pages", "losa_sparse_attn", "losa_step", "losa_profile_enable",
+           "losa_profile_read"]
+STAGES = ["locality", "score", "topk", "attn", "merge", "bounds"]
 
 
 class LosaError(RuntimeError):
@@ -70,6 +72,10 @@ def load_library() -> C.CDLL:
     lib.losa_sparse_attn.argtypes = [vp, vp, C.POINTER(losa_kv), p, p, p, p, p, i32, p, p]
     lib.losa_step.restype = C.c_int
     lib.losa_step.argtypes = [vp, vp, C.POINTER(losa_kv), i32, p, p, p, C.c_int, f32, i32, p, p, p, p]
+    lib.losa_profile_enable.restype = C.c_int
+    lib.losa_profile_enable.argtypes = [vp, i32]
+    lib.losa_profile_read.restype = C.c_int
+    lib.losa_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     _lib = lib
     return lib
 
@@ -190,3 +196,15 @@ def losa_step(ctx: Context, kv: PagedKV, step_index: int, h_cur, h_prev, q, mode
     _check(ctx, load_library().losa_step(ctx.handle, _stream(stream), C.byref(s), step_index, _ptr(h_cur),
                                         _ptr(h_prev), _ptr(q), mode, param, topk_pages, _ptr(o_p), _ptr(lse_p),
                                         _ptr(mask), _ptr(sel_count)))
+
+
+def losa_profile_enable(ctx: Context, enable: bool):
+    _check(ctx, load_library().losa_profile_enable(ctx.handle, 1 if enable else 0))
+
+
+def losa_profile_read(ctx: Context):
+    """-> ({stage: milliseconds}, {stage: launches}) since the last read."""
+    ms = (C.c_double * len(STAGES))()
+    cnt = (C.c_int64 * len(STAGES))()
+    _check(ctx, load_library().losa_profile_read(ctx.handle, ms, cnt))
+    return dict(zip(STAGES, list(ms))), dict(zip(STAGES, list(cnt)))

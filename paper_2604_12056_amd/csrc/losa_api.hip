@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <new>
+#include <vector>
 
 #include "losa_internal.h"
 
@@ -26,12 +27,17 @@ struct losa_ctx {
   Partials part;
   long part_items;
   char err[256];
+  // measurement hooks
+  bool profiling = false;
+  std::vector<hipEvent_t> events;   // pool, used in pairs
+  std::vector<int> rec_stage;       // stage of pair i
+  size_t rec_used = 0;              // pairs recorded since the last read
 };
 
 namespace {
 
-constexpr long kTargetItems = 1024;  // split-K work items aimed at per attention launch (4 per CU)
-constexpr int kMinChunkPages = 2;
+constexpr long kTargetItems = 1024;       // capacity of the split-K partial buffers, in work items
+constexpr long kTargetWorkgroups = 256;   // attention workgroups aimed at per launch: one per CU
 
 thread_local char g_create_err[256] = "";
 
@@ -109,6 +115,24 @@ Layout make_layout(const losa_config* c) {
 
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+constexpr size_t kMaxProfilePairs = 16384;
+
+// Brackets the launches made in its scope with a pair of events when profiling is on.
+struct StageTimer {
+  losa_ctx* ctx;
+  hipStream_t st;
+  size_t pair = (size_t)-1;
+  StageTimer(losa_ctx* c, hipStream_t s, int stage) : ctx(c), st(s) {
+    if (!ctx->profiling || ctx->rec_used >= kMaxProfilePairs) return;
+    pair = ctx->rec_used++;
+    ctx->rec_stage[pair] = stage;
+    (void)hipEventRecord(ctx->events[2 * pair], st);
+  }
+  ~StageTimer() {
+    if (pair != (size_t)-1) (void)hipEventRecord(ctx->events[2 * pair + 1], st);
+  }
+};
+
 losa_status check_kv(losa_ctx* ctx, const losa_kv* kv, bool need_meta, int* max_seq_pages) {
   if (!kv) return fail(ctx, LOSA_ERR_INVALID_ARG, "kv is NULL");
   if (kv->batch < 1 || kv->batch > ctx->cfg.max_batch)
@@ -116,7 +140,7 @@ losa_status check_kv(losa_ctx* ctx, const losa_kv* kv, bool need_meta, int* max_
   if (!kv->k_pages || !kv->v_pages || !kv->page_indptr || !kv->page_indices || !kv->seq_lens)
     return fail(ctx, LOSA_ERR_INVALID_ARG, "kv has a NULL device pointer");
   if (need_meta && !kv->meta) return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.meta is NULL");
-  if (kv->num_pages < 0) return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.num_pages is negative");
+  if (kv->num_pages < 1) return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.num_pages must be >= 1");
   if (kv->max_seq_pages < 0 || kv->max_seq_pages > ctx->cfg.max_pages_per_seq)
     return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.max_seq_pages %d outside 0..max_pages_per_seq (%d)", kv->max_seq_pages,
                 ctx->cfg.max_pages_per_seq);
@@ -140,18 +164,24 @@ losa_status hip_fail(losa_ctx* ctx, const char* what, hipError_t e) {
   return fail(ctx, LOSA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-// Number of page chunks per (sequence, KV head) list of at most `upper` pages.
-void pick_chunks(const losa_ctx* ctx, int batch, int upper, int* chunk_pages, int* nchunk) {
+// Number of equal shares a (sequence, KV head) page list of at most `upper` pages is split into.
+int pick_nchunk(const losa_ctx* ctx, int batch, int upper, int row_groups) {
   const long heads = (long)batch * ctx->sh.Hkv;
-  long want = ctx->part_items / heads;
+  const long tiles = (upper + (32 / ctx->sh.g) - 1) / (32 / ctx->sh.g);
+  long want = kTargetWorkgroups / (heads * row_groups);
+  const long fit = ctx->part_items / heads;
+  if (want > fit) want = fit;
+  if (want > tiles) want = tiles;
   if (want < 1) want = 1;
-  const int step = 32 / ctx->sh.g;  // whole 32-token tiles
-  long cp = (upper + want - 1) / want;
-  if (cp < kMinChunkPages) cp = kMinChunkPages;
-  cp = (cp + step - 1) / step * step;
-  *chunk_pages = (int)cp;
-  *nchunk = (int)((upper + cp - 1) / cp);
-  if (*nchunk < 1) *nchunk = 1;
+  return (int)want;
+}
+
+// |A| for the top-n modes (TOPK, FRACTION); the caller has validated param.
+int select_count(const losa_ctx* ctx, int mode, float param) {
+  const int B = ctx->sh.B;
+  if (mode == LOSA_SEL_TOPK) return param >= (float)B ? B : (int)param;
+  int n = (int)floorf(param * (float)B + 0.5f);
+  return n < 1 ? 1 : (n > B ? B : n);
 }
 
 losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const void* h_cur, const void* h_prev,
@@ -162,17 +192,17 @@ losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const v
   float tau = 0.f;
   if (mode == LOSA_SEL_TOPK) {
     if (!(param >= 0.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "top-k parameter must be >= 0");
-    n = param >= (float)B ? B : (int)param;
+    n = select_count(ctx, mode, param);
   } else if (mode == LOSA_SEL_FRACTION) {
     if (!(param >= 0.f && param <= 1.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "fraction must be in [0,1]");
-    n = (int)floorf(param * (float)B + 0.5f);
-    n = n < 1 ? 1 : (n > B ? B : n);
+    n = select_count(ctx, mode, param);
   } else if (mode == LOSA_SEL_THRESHOLD) {
     if (isnan(param)) return fail(ctx, LOSA_ERR_INVALID_ARG, "threshold is NaN");
     tau = param;
   } else {
     return fail(ctx, LOSA_ERR_INVALID_ARG, "unknown select mode %d", mode);
   }
+  StageTimer timer(ctx, st, LOSA_STAGE_LOCALITY);
   hipError_t e = launch_locality_delta(st, ctx->cfg.dtype, h_cur, h_prev, batch * B, ctx->sh.H, delta);
   if (e != hipSuccess) return hip_fail(ctx, "locality_delta launch", e);
   e = launch_rank_select(st, delta, batch, B, mode, n, tau, mask, active_idx, active_count);
@@ -183,9 +213,14 @@ losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const v
 losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
                              const void* q, const int32_t* active_idx, const int32_t* active_count, int topk,
                              int32_t* topk_out, int32_t* sel_pages, int32_t* sel_count, int cap) {
-  hipError_t e = launch_page_scores(st, ctx->cfg.dtype, kv, ctx->sh, batch, max_seq_pages, q, active_idx,
-                                    active_count, ctx->scores, ctx->bitmap);
+  hipError_t e;
+  {
+    StageTimer timer(ctx, st, LOSA_STAGE_SCORE);
+    e = launch_page_scores(st, ctx->cfg.dtype, kv, ctx->sh, batch, max_seq_pages, q, active_idx, active_count,
+                           ctx->scores, ctx->bitmap);
+  }
   if (e != hipSuccess) return hip_fail(ctx, "page_scores launch", e);
+  StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
   e = launch_topk_union(st, kv, ctx->sh, batch, max_seq_pages, active_count, ctx->scores, topk, topk_out, ctx->bitmap);
   if (e != hipSuccess) return hip_fail(ctx, "topk_union launch", e);
   e = launch_union_compact(st, kv, ctx->sh, batch, max_seq_pages, active_count, ctx->bitmap, sel_pages, sel_count, cap);
@@ -195,15 +230,28 @@ losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
 
 losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
                              const void* q, const int32_t* active_idx, const int32_t* active_count,
-                             const int32_t* sel_pages, const int32_t* sel_count, int cap, float* o_p, float* lse_p) {
+                             const int32_t* sel_pages, const int32_t* sel_count, int cap, int rows_upper, float* o_p,
+                             float* lse_p) {
   const int upper = sel_pages ? (cap < max_seq_pages ? cap : max_seq_pages) : max_seq_pages;
-  int chunk_pages, nchunk;
-  pick_chunks(ctx, batch, upper, &chunk_pages, &nchunk);
-  hipError_t e = launch_attn_partials(st, ctx->cfg.dtype, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages,
-                                      sel_count, cap, chunk_pages, nchunk, ctx->part);
-  if (e != hipSuccess) return hip_fail(ctx, "attn_partials launch", e);
-  e = launch_attn_merge(st, kv, ctx->sh, batch, active_idx, active_count, sel_count, cap, chunk_pages, nchunk,
-                        /*log2_units=*/false, ctx->part, o_p, lse_p);
+  const bool mfma = ctx->cfg.dtype == LOSA_BF16;
+  if (rows_upper < 1 || rows_upper > ctx->sh.rows_max) rows_upper = ctx->sh.rows_max;
+  // matrix-core kernel: up to 64 rows ride in one workgroup; more rows -> groups of 4 x 64 rows
+  const int row_groups = mfma ? (rows_upper <= 64 ? 1 : (ctx->sh.rows_max + 255) / 256) : (ctx->sh.rows_max + 31) / 32;
+  const int nchunk = pick_nchunk(ctx, batch, upper, mfma ? row_groups : 1);
+  hipError_t e;
+  {
+    StageTimer timer(ctx, st, LOSA_STAGE_ATTN);
+    if (mfma)
+      e = launch_attn_mfma(st, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages, sel_count, cap, nchunk,
+                           rows_upper, ctx->part);
+    else
+      e = launch_attn_generic(st, ctx->cfg.dtype, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages,
+                              sel_count, cap, nchunk, ctx->part);
+  }
+  if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
+  StageTimer timer(ctx, st, LOSA_STAGE_MERGE);
+  e = launch_attn_merge(st, kv, ctx->sh, batch, active_idx, active_count, sel_count, cap, nchunk, mfma, ctx->part,
+                        o_p, lse_p);
   if (e != hipSuccess) return hip_fail(ctx, "attn_merge launch", e);
   return LOSA_OK;
 }
@@ -261,7 +309,50 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
 }
 
 losa_status losa_destroy(losa_ctx* ctx) {
+  if (ctx) losa_profile_enable(ctx, 0);
   delete ctx;
+  return LOSA_OK;
+}
+
+losa_status losa_profile_enable(losa_ctx* ctx, int32_t enable) {
+  if (!ctx) return LOSA_ERR_INVALID_ARG;
+  if (enable && ctx->events.empty()) {
+    ctx->events.resize(2 * kMaxProfilePairs, nullptr);
+    ctx->rec_stage.assign(kMaxProfilePairs, 0);
+    for (size_t i = 0; i < ctx->events.size(); ++i) {
+      hipError_t e = hipEventCreate(&ctx->events[i]);
+      if (e != hipSuccess) {
+        for (size_t k = 0; k < i; ++k) (void)hipEventDestroy(ctx->events[k]);
+        ctx->events.clear();
+        return hip_fail(ctx, "hipEventCreate", e);
+      }
+    }
+  }
+  if (!enable && !ctx->events.empty()) {
+    for (hipEvent_t ev : ctx->events) (void)hipEventDestroy(ev);
+    ctx->events.clear();
+  }
+  ctx->profiling = enable != 0;
+  ctx->rec_used = 0;
+  return LOSA_OK;
+}
+
+losa_status losa_profile_read(losa_ctx* ctx, double* stage_ms, int64_t* stage_launches) {
+  if (!ctx || !stage_ms || !stage_launches) return LOSA_ERR_INVALID_ARG;
+  for (int s = 0; s < LOSA_NUM_STAGES; ++s) {
+    stage_ms[s] = 0.0;
+    stage_launches[s] = 0;
+  }
+  for (size_t i = 0; i < ctx->rec_used; ++i) {
+    hipError_t e = hipEventSynchronize(ctx->events[2 * i + 1]);
+    if (e != hipSuccess) return hip_fail(ctx, "hipEventSynchronize", e);
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, ctx->events[2 * i], ctx->events[2 * i + 1]);
+    if (e != hipSuccess) return hip_fail(ctx, "hipEventElapsedTime", e);
+    stage_ms[ctx->rec_stage[i]] += ms;
+    stage_launches[ctx->rec_stage[i]] += 1;
+  }
+  ctx->rec_used = 0;
   return LOSA_OK;
 }
 
@@ -289,6 +380,7 @@ losa_status losa_page_bounds(losa_ctx* ctx, void* stream, const losa_kv* kv, int
   int n = msp - first_logical_page;
   if (num_logical_pages >= 0 && num_logical_pages < n) n = num_logical_pages;
   if (n <= 0) return LOSA_OK;
+  StageTimer timer(ctx, as_stream(stream), LOSA_STAGE_BOUNDS);
   hipError_t e = launch_page_bounds(as_stream(stream), ctx->cfg.dtype, view_of(kv), ctx->sh, kv->batch,
                                     first_logical_page, n);
   if (e != hipSuccess) return hip_fail(ctx, "page_bounds launch", e);
@@ -328,7 +420,7 @@ losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, con
     return fail(ctx, LOSA_ERR_INVALID_ARG, "sel_pages and sel_count must both be given or both be NULL");
   if (sel_pages && cap < 1) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap must be >= 1");
   return sparse_attn_impl(ctx, as_stream(stream), view_of(kv), kv->batch, msp, q, active_idx, active_count, sel_pages,
-                          sel_count, cap, (float*)o_p, lse_p);
+                          sel_count, cap, /*rows_upper=*/0, (float*)o_p, lse_p);
 }
 
 losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t step_index, const void* h_cur,
@@ -344,7 +436,7 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
   hipStream_t st = as_stream(stream);
   const KvView view = view_of(kv);
   if (dense)
-    return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, nullptr, nullptr, nullptr, nullptr, 0, (float*)o_p, lse_p);
+    return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, nullptr, nullptr, nullptr, nullptr, 0, 0, (float*)o_p, lse_p);
   if (!h_cur || !h_prev) return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_step: h_cur / h_prev are NULL");
   if (topk_pages < 1 || topk_pages > ctx->cfg.max_topk_pages)
     return fail(ctx, LOSA_ERR_INVALID_ARG, "topk_pages %d outside 1..max_topk_pages (%d)", topk_pages,
@@ -358,8 +450,10 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
   s = score_pages_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, topk_pages, nullptr,
                        ctx->sel_pages, sc, cap);
   if (s != LOSA_OK) return s;
+  // the host knows |A| in the top-n modes, so the attention can be shaped for n*G rows
+  const int rows_upper = mode == LOSA_SEL_THRESHOLD ? 0 : select_count(ctx, (int)mode, param) * ctx->sh.G;
   return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, ctx->sel_pages, sc,
-                          cap, (float*)o_p, lse_p);
+                          cap, rows_upper, (float*)o_p, lse_p);
 }
 
 }  // extern "C"

@@ -56,14 +56,18 @@ hipError_t launch_union_compact(hipStream_t st, const KvView& kv, const Shape& s
                                 const int32_t* active_count, const uint32_t* bitmap,
                                 int32_t* sel_pages, int32_t* sel_count, int cap);
 
-// ---- sparse_attn.hip
-hipError_t launch_attn_partials(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
-                                const void* q, const int32_t* active_idx, const int32_t* active_count,
-                                const int32_t* sel_pages, const int32_t* sel_count, int cap,
-                                int chunk_pages, int nchunk, const Partials& part);
+// ---- sparse_attn.hip (element-generic kernel, merge) and sparse_attn_mfma.hip (bfloat16 matrix-core kernel)
+// Both split a (sequence, KV head) page list into `nchunk` equal shares of its actual length.
+hipError_t launch_attn_generic(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
+                               const void* q, const int32_t* active_idx, const int32_t* active_count,
+                               const int32_t* sel_pages, const int32_t* sel_count, int cap, int nchunk,
+                               const Partials& part);
+hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
+                            const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
+                            const int32_t* sel_count, int cap, int nchunk, int rows_upper, const Partials& part);
 hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch,
                              const int32_t* active_idx, const int32_t* active_count,
-                             const int32_t* sel_count, int cap, int chunk_pages, int nchunk, bool log2_units,
+                             const int32_t* sel_count, int cap, int nchunk, bool log2_units,
                              const Partials& part, float* o_p, float* lse_p);
 
 }  // namespace losa

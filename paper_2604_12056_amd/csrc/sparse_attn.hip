@@ -12,6 +12,8 @@
 // float); it serves the float mode and is the fallback shape for bfloat16.
 #include <math.h>
 
+#include <type_traits>
+
 #include "losa_device.h"
 #include "losa_internal.h"
 
@@ -32,7 +34,7 @@ template <typename T, int D, int GP>
 __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
     KvView kv, Shape sh, const T* __restrict__ q, const int32_t* __restrict__ active_idx,
     const int32_t* __restrict__ active_count, const int32_t* __restrict__ sel_pages,
-    const int32_t* __restrict__ sel_count, int cap, int chunk_pages, int nchunk, int nrb, Partials part) {
+    const int32_t* __restrict__ sel_count, int cap, int nchunk, int nrb, Partials part) {
   constexpr int V = Vec16<T>::n;
   constexpr int VPR = D / V;           // 16-byte vectors per key row
   constexpr int PPT = kTileTok / GP;   // pages per tile
@@ -53,9 +55,11 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
   const int L = kv.seq_lens[b];
   const int32_t* list = sel_pages ? sel_pages + ((size_t)b * sh.Hkv + j) * cap : nullptr;
   const int U = list ? min(sel_count[b * sh.Hkv + j], cap) : P;
-  const int c0 = chunk * chunk_pages;
-  if (c0 >= U) return;
-  const int c1 = min(U, c0 + chunk_pages);
+  const int ntiles = (U + PPT - 1) / PPT;
+  const int tpc = (ntiles + nchunk - 1) / nchunk;   // tiles per chunk: equal shares of the real list
+  const int tile0 = chunk * tpc, tile1 = min(ntiles, tile0 + tpc);
+  if (tile0 >= tile1) return;
+  const int c0 = tile0 * PPT, c1 = min(U, tile1 * PPT);
 
   for (int v = tid; v < kRowBlock * VPR; v += 256) {
     const int rr = v / VPR, cv = v % VPR, r = r0 + rr;
@@ -188,15 +192,25 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
   }
 }
 
-// Combine the chunk partials of one query row.  LOG2: partial maxima are in log2 units
-// (scores were scaled by sm_scale*log2(e)); otherwise natural units.
+// Combine the chunk partials of one query row with the log-sum-exp rule, normalise, and
+// write (o_p, lse_p) at the active token's row.  256 threads = CL chunk lanes x D/4 channel
+// quads: every chunk lane sums its chunks c = lane, lane+CL, ... (independent loads), then
+// the lanes are added in a fixed order, so the result does not depend on scheduling.
+// LOG2: partial maxima are in log2 units (scores scaled by sm_scale*log2(e)) and sums are
+// float; otherwise natural units and double sums (the element-generic kernel, which also
+// serves the float mode).
 template <int D, bool LOG2>
-__global__ __launch_bounds__(D) void attn_merge_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_idx,
-                                                       const int32_t* __restrict__ active_count,
-                                                       const int32_t* __restrict__ sel_count, int cap, int chunk_pages,
-                                                       int nchunk, Partials part, float* __restrict__ o_p,
-                                                       float* __restrict__ lse_p) {
-  const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, ch = threadIdx.x;
+__global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_idx,
+                                                         const int32_t* __restrict__ active_count,
+                                                         const int32_t* __restrict__ sel_count, int cap, int nchunk,
+                                                         Partials part, float* __restrict__ o_p,
+                                                         float* __restrict__ lse_p) {
+  typedef typename std::conditional<LOG2, float, double>::type Acc;
+  constexpr int C4 = D / 4, CL = 256 / C4;
+  __shared__ Acc red[CL][D];
+  __shared__ Acc lred[CL];
+  __shared__ float wmax[4];
+  const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
   const int n = active_idx ? min(active_count[b], sh.B) : sh.B;
   if (r >= n * sh.G) return;
   const int a = r / sh.G, hg = r % sh.G;
@@ -204,85 +218,101 @@ __global__ __launch_bounds__(D) void attn_merge_kernel(KvView kv, Shape sh, cons
   if ((unsigned)tok >= (unsigned)sh.B) return;
   const int P = min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages);
   const int U = sel_count ? min(sel_count[b * sh.Hkv + j], cap) : P;
-  const int live = min(nchunk, (U + chunk_pages - 1) / chunk_pages);
+  const int ppt = 32 / sh.g;
+  const int ntiles = (U + ppt - 1) / ppt;
+  const int tpc = (ntiles + nchunk - 1) / nchunk;
+  const int live = ntiles > 0 ? (ntiles + tpc - 1) / tpc : 0;
   const size_t item0 = ((size_t)b * sh.Hkv + j) * nchunk;
-  float m_tot = -INFINITY;
-  for (int c = 0; c < live; ++c) m_tot = fmaxf(m_tot, part.m[(item0 + c) * sh.rows_max + r]);
+
+  float mx = -INFINITY;
+  for (int c = tid; c < live; c += 256) mx = fmaxf(mx, part.m[(item0 + c) * sh.rows_max + r]);
+  mx = wave_max(mx);
+  if ((tid & 63) == 0) wmax[tid >> 6] = mx;
+  __syncthreads();
+  const float m_tot = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
   const size_t orow = ((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + hg;
-  if (m_tot == -INFINITY) {   // no valid token at all
-    o_p[orow * D + ch] = 0.f;
-    if (ch == 0) lse_p[orow] = -INFINITY;
+  if (!(m_tot > -1.0e29f)) {   // no valid token at all: the neutral element of the merge
+    if (tid < C4) reinterpret_cast<float4*>(o_p + orow * D)[tid] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (tid == 0) lse_p[orow] = -INFINITY;
     return;
   }
-  if (LOG2) {
-    float l = 0.f, o = 0.f;
-    for (int c = 0; c < live; ++c) {
-      const size_t prow = (item0 + c) * sh.rows_max + r;
-      const float w = exp2f(part.m[prow] - m_tot);
-      l = fmaf(part.l[prow], w, l);
-      o = fmaf(part.o[prow * D + ch], w, o);
+  const int cl = tid / C4, c4 = tid % C4;
+  Acc ax = 0, ay = 0, az = 0, aw = 0, lacc = 0;
+  for (int c = cl; c < live; c += CL) {
+    const size_t prow = (item0 + c) * sh.rows_max + r;
+    const float dm = part.m[prow] - m_tot;
+    const Acc w = LOG2 ? (Acc)exp2f(dm) : (Acc)exp((double)dm);
+    const float4 v = reinterpret_cast<const float4*>(part.o + prow * D)[c4];
+    ax += w * (Acc)v.x;
+    ay += w * (Acc)v.y;
+    az += w * (Acc)v.z;
+    aw += w * (Acc)v.w;
+    lacc += w * (Acc)part.l[prow];
+  }
+  red[cl][c4 * 4 + 0] = ax;
+  red[cl][c4 * 4 + 1] = ay;
+  red[cl][c4 * 4 + 2] = az;
+  red[cl][c4 * 4 + 3] = aw;
+  if (c4 == 0) lred[cl] = lacc;
+  __syncthreads();
+  if (tid < D) {
+    Acc o = 0, l = 0;
+#pragma unroll
+    for (int k = 0; k < CL; ++k) {
+      o += red[k][tid];
+      l += lred[k];
     }
-    o_p[orow * D + ch] = o / l;
-    if (ch == 0) lse_p[orow] = (m_tot + log2f(l)) * 0.6931471805599453f;
-  } else {   // natural units: the generic kernel, which also serves the float mode; combine in double
-    double l = 0., o = 0.;
-    for (int c = 0; c < live; ++c) {
-      const size_t prow = (item0 + c) * sh.rows_max + r;
-      const double w = exp((double)part.m[prow] - (double)m_tot);
-      l += (double)part.l[prow] * w;
-      o += (double)part.o[prow * D + ch] * w;
-    }
-    o_p[orow * D + ch] = (float)(o / l);
-    if (ch == 0) lse_p[orow] = (float)((double)m_tot + log(l));
+    o_p[orow * D + tid] = (float)(o / l);
+    if (tid == 0)
+      lse_p[orow] = LOG2 ? (m_tot + log2f((float)l)) * 0.6931471805599453f : (float)((double)m_tot + log((double)l));
   }
 }
 
 template <typename T, int D>
 static hipError_t launch_generic(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
                                  const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
-                                 const int32_t* sel_count, int cap, int chunk_pages, int nchunk,
-                                 const Partials& part) {
+                                 const int32_t* sel_count, int cap, int nchunk, const Partials& part) {
   const int nrb = (sh.rows_max + kRowBlock - 1) / kRowBlock;
   dim3 grid(nchunk, sh.Hkv * nrb, batch);
   if (sh.g == 16)
     attn_partials_generic_kernel<T, D, 16><<<grid, 256, 0, st>>>(kv, sh, (const T*)q, active_idx, active_count,
-                                                                 sel_pages, sel_count, cap, chunk_pages, nchunk, nrb, part);
+                                                                 sel_pages, sel_count, cap, nchunk, nrb, part);
   else
     attn_partials_generic_kernel<T, D, 32><<<grid, 256, 0, st>>>(kv, sh, (const T*)q, active_idx, active_count,
-                                                                 sel_pages, sel_count, cap, chunk_pages, nchunk, nrb, part);
+                                                                 sel_pages, sel_count, cap, nchunk, nrb, part);
   return hipGetLastError();
 }
 
-hipError_t launch_attn_partials(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch, const void* q,
-                                const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
-                                const int32_t* sel_count, int cap, int chunk_pages, int nchunk, const Partials& part) {
+hipError_t launch_attn_generic(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch, const void* q,
+                               const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
+                               const int32_t* sel_count, int cap, int nchunk, const Partials& part) {
   if (batch <= 0 || nchunk <= 0) return hipSuccess;
   if (dtype == LOSA_BF16)
     return sh.d == 128 ? launch_generic<bf16_t, 128>(st, kv, sh, batch, q, active_idx, active_count, sel_pages,
-                                                     sel_count, cap, chunk_pages, nchunk, part)
+                                                     sel_count, cap, nchunk, part)
                        : launch_generic<bf16_t, 64>(st, kv, sh, batch, q, active_idx, active_count, sel_pages,
-                                                    sel_count, cap, chunk_pages, nchunk, part);
+                                                    sel_count, cap, nchunk, part);
   return sh.d == 128 ? launch_generic<float, 128>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count,
-                                                  cap, chunk_pages, nchunk, part)
+                                                  cap, nchunk, part)
                      : launch_generic<float, 64>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count,
-                                                 cap, chunk_pages, nchunk, part);
+                                                 cap, nchunk, part);
 }
 
 hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const int32_t* active_idx,
-                             const int32_t* active_count, const int32_t* sel_count, int cap, int chunk_pages,
-                             int nchunk, bool log2_units, const Partials& part, float* o_p, float* lse_p) {
+                             const int32_t* active_count, const int32_t* sel_count, int cap, int nchunk,
+                             bool log2_units, const Partials& part, float* o_p, float* lse_p) {
   if (batch <= 0) return hipSuccess;
   dim3 grid(sh.rows_max, sh.Hkv, batch);
   if (sh.d == 128) {
     if (log2_units)
-      attn_merge_kernel<128, true><<<grid, 128, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, chunk_pages, nchunk, part, o_p, lse_p);
+      attn_merge_kernel<128, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, part, o_p, lse_p);
     else
-      attn_merge_kernel<128, false><<<grid, 128, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, chunk_pages, nchunk, part, o_p, lse_p);
+      attn_merge_kernel<128, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, part, o_p, lse_p);
   } else {
     if (log2_units)
-      attn_merge_kernel<64, true><<<grid, 64, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, chunk_pages, nchunk, part, o_p, lse_p);
+      attn_merge_kernel<64, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, part, o_p, lse_p);
     else
-      attn_merge_kernel<64, false><<<grid, 64, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, chunk_pages, nchunk, part, o_p, lse_p);
+      attn_merge_kernel<64, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, part, o_p, lse_p);
   }
   return hipGetLastError();
 }
