@@ -66,7 +66,7 @@ typedef struct {
   int32_t hidden_size;       /* H: row length of the tensor the detector compares; multiple of 8 */
   int32_t page_size;         /* g: 16 or 32 */
   int32_t block_size;        /* B: 1..256 */
-  int32_t max_pages_per_seq; /* upper bound on P_b */
+  int32_t max_pages_per_seq; /* upper bound on P_b, 1..16384 */
   int32_t max_topk_pages;    /* upper bound on the per-query page budget K = k/g */
   int32_t dtype;             /* losa_dtype */
   float sm_scale;            /* score scale; 0 means 1/sqrt(d) */

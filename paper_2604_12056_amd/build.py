@@ -15,6 +15,9 @@ SOURCES = ["losa_api.hip", "select_active.hip", "page_bounds.hip", "score_pages.
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # keep packed-fp32 VALU forms out of the device code
+    # matrix-core accumulators in ordinary vector registers: the online-softmax rescale is plain
+    # vector arithmetic on them, and the accumulator-register form costs a copy in and out per tile
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

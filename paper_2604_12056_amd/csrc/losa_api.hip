@@ -21,11 +21,13 @@ struct losa_ctx {
   int32_t* active_idx;
   int32_t* active_count;
   float* scores;
-  uint32_t* bitmap;
+  uint32_t* rowmaps;
+  int32_t* tickets;
   int32_t* sel_pages;
   int32_t* sel_count;
   Partials part;
   long part_items;
+  AttnPrepared prep;
   char err[256];
   // measurement hooks
   bool profiling = false;
@@ -66,7 +68,7 @@ bool config_problem(const losa_config* c, char* why, size_t n) {
   BAD(c->page_size != 16 && c->page_size != 32, "page_size must be 16 or 32");
   BAD(c->block_size < 1 || c->block_size > 256, "block_size must be in 1..256");
   BAD(c->hidden_size < 8 || c->hidden_size % 8 != 0, "hidden_size must be a positive multiple of 8");
-  BAD(c->max_pages_per_seq < 1, "max_pages_per_seq must be >= 1");
+  BAD(c->max_pages_per_seq < 1 || c->max_pages_per_seq > kMaxSelectPages, "max_pages_per_seq must be in 1..16384");
   BAD(c->max_topk_pages < 1, "max_topk_pages must be >= 1");
   BAD(c->dtype != LOSA_BF16 && c->dtype != LOSA_F32, "dtype must be LOSA_BF16 or LOSA_F32");
   BAD(!(c->sm_scale >= 0.f) || isinf(c->sm_scale), "sm_scale must be finite and >= 0");
@@ -85,7 +87,8 @@ struct Carve {
 };
 
 struct Layout {
-  size_t delta, mask, active_idx, active_count, scores, bitmap, sel_pages, sel_count, po, pm, pl, total;
+  size_t delta, mask, active_idx, active_count, scores, rowmaps, tickets, sel_pages, sel_count, po, pm, pl;
+  size_t entries, q_act, ucount, mrows, total;
   long part_items;
 };
 
@@ -103,12 +106,17 @@ Layout make_layout(const losa_config* c) {
   L.active_idx = cv.take(rows * 4);
   L.active_count = cv.take((size_t)c->max_batch * 4);
   L.scores = cv.take(heads * rows_max * c->max_pages_per_seq * 4);
-  L.bitmap = cv.take(heads * words * 4);
+  L.rowmaps = cv.take(heads * rows_max * words * 4);
+  L.tickets = cv.take(heads * 4);
   L.sel_pages = cv.take(heads * c->max_pages_per_seq * 4);
   L.sel_count = cv.take(heads * 4);
   L.po = cv.take((size_t)L.part_items * rows_max * c->head_dim * 4);
   L.pm = cv.take((size_t)L.part_items * rows_max * 4);
   L.pl = cv.take((size_t)L.part_items * rows_max * 4);
+  L.entries = cv.take(heads * c->max_pages_per_seq * 4);
+  L.q_act = cv.take(heads * rows_max * c->head_dim * 2);
+  L.ucount = cv.take(heads * 4);
+  L.mrows = cv.take(heads * 4);
   L.total = cv.off;
   return L;
 }
@@ -140,7 +148,8 @@ losa_status check_kv(losa_ctx* ctx, const losa_kv* kv, bool need_meta, int* max_
   if (!kv->k_pages || !kv->v_pages || !kv->page_indptr || !kv->page_indices || !kv->seq_lens)
     return fail(ctx, LOSA_ERR_INVALID_ARG, "kv has a NULL device pointer");
   if (need_meta && !kv->meta) return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.meta is NULL");
-  if (kv->num_pages < 1) return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.num_pages must be >= 1");
+  if (kv->num_pages < 1 || kv->num_pages > (1 << kEntryShift))
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.num_pages must be in 1..2^26");
   if (kv->max_seq_pages < 0 || kv->max_seq_pages > ctx->cfg.max_pages_per_seq)
     return fail(ctx, LOSA_ERR_INVALID_ARG, "kv.max_seq_pages %d outside 0..max_pages_per_seq (%d)", kv->max_seq_pages,
                 ctx->cfg.max_pages_per_seq);
@@ -212,26 +221,26 @@ losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const v
 
 losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
                              const void* q, const int32_t* active_idx, const int32_t* active_count, int topk,
-                             int32_t* topk_out, int32_t* sel_pages, int32_t* sel_count, int cap) {
+                             int32_t* topk_out, int32_t* sel_pages, int32_t* sel_count, int cap, bool prepare_attn) {
+  const AttnPrepared* prep = prepare_attn ? &ctx->prep : nullptr;
   hipError_t e;
   {
     StageTimer timer(ctx, st, LOSA_STAGE_SCORE);
     e = launch_page_scores(st, ctx->cfg.dtype, kv, ctx->sh, batch, max_seq_pages, q, active_idx, active_count,
-                           ctx->scores, ctx->bitmap);
+                           ctx->scores, ctx->tickets, sel_count, prep);
   }
   if (e != hipSuccess) return hip_fail(ctx, "page_scores launch", e);
   StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
-  e = launch_topk_union(st, kv, ctx->sh, batch, max_seq_pages, active_count, ctx->scores, topk, topk_out, ctx->bitmap);
-  if (e != hipSuccess) return hip_fail(ctx, "topk_union launch", e);
-  e = launch_union_compact(st, kv, ctx->sh, batch, max_seq_pages, active_count, ctx->bitmap, sel_pages, sel_count, cap);
-  if (e != hipSuccess) return hip_fail(ctx, "union_compact launch", e);
+  e = launch_select_pages(st, kv, ctx->sh, batch, max_seq_pages, q, active_idx, active_count, ctx->scores, topk,
+                          topk_out, sel_pages, sel_count, cap, ctx->rowmaps, ctx->tickets, prep);
+  if (e != hipSuccess) return hip_fail(ctx, "select_pages launch", e);
   return LOSA_OK;
 }
 
 losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
                              const void* q, const int32_t* active_idx, const int32_t* active_count,
-                             const int32_t* sel_pages, const int32_t* sel_count, int cap, int rows_upper, float* o_p,
-                             float* lse_p) {
+                             const int32_t* sel_pages, const int32_t* sel_count, int cap, int rows_upper,
+                             bool prepared, float* o_p, float* lse_p) {
   const int upper = sel_pages ? (cap < max_seq_pages ? cap : max_seq_pages) : max_seq_pages;
   const bool mfma = ctx->cfg.dtype == LOSA_BF16;
   if (rows_upper < 1 || rows_upper > ctx->sh.rows_max) rows_upper = ctx->sh.rows_max;
@@ -239,19 +248,23 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   const int row_groups = mfma ? (rows_upper <= 64 ? 1 : (ctx->sh.rows_max + 255) / 256) : (ctx->sh.rows_max + 31) / 32;
   const int nchunk = pick_nchunk(ctx, batch, upper, mfma ? row_groups : 1);
   hipError_t e;
+  if (mfma && !prepared) {
+    StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
+    e = launch_attn_prepare(st, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages, sel_count, cap, ctx->prep);
+    if (e != hipSuccess) return hip_fail(ctx, "attn_prepare launch", e);
+  }
   {
     StageTimer timer(ctx, st, LOSA_STAGE_ATTN);
     if (mfma)
-      e = launch_attn_mfma(st, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages, sel_count, cap, nchunk,
-                           rows_upper, ctx->part);
+      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, rows_upper, ctx->part);
     else
       e = launch_attn_generic(st, ctx->cfg.dtype, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages,
                               sel_count, cap, nchunk, ctx->part);
   }
   if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
   StageTimer timer(ctx, st, LOSA_STAGE_MERGE);
-  e = launch_attn_merge(st, kv, ctx->sh, batch, active_idx, active_count, sel_count, cap, nchunk, mfma, ctx->part,
-                        o_p, lse_p);
+  e = launch_attn_merge(st, kv, ctx->sh, batch, active_idx, active_count, sel_count, cap, nchunk,
+                        mfma ? &ctx->prep : nullptr, ctx->part, o_p, lse_p);
   if (e != hipSuccess) return hip_fail(ctx, "attn_merge launch", e);
   return LOSA_OK;
 }
@@ -296,13 +309,18 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   ctx->active_idx = (int32_t*)(base + L.active_idx);
   ctx->active_count = (int32_t*)(base + L.active_count);
   ctx->scores = (float*)(base + L.scores);
-  ctx->bitmap = (uint32_t*)(base + L.bitmap);
+  ctx->rowmaps = (uint32_t*)(base + L.rowmaps);
+  ctx->tickets = (int32_t*)(base + L.tickets);
   ctx->sel_pages = (int32_t*)(base + L.sel_pages);
   ctx->sel_count = (int32_t*)(base + L.sel_count);
   ctx->part.o = (float*)(base + L.po);
   ctx->part.m = (float*)(base + L.pm);
   ctx->part.l = (float*)(base + L.pl);
   ctx->part_items = L.part_items;
+  ctx->prep.entries = (int32_t*)(base + L.entries);
+  ctx->prep.q_act = (uint16_t*)(base + L.q_act);
+  ctx->prep.ucount = (int32_t*)(base + L.ucount);
+  ctx->prep.mrows = (int32_t*)(base + L.mrows);
   ctx->err[0] = 0;
   *out = ctx;
   return LOSA_OK;
@@ -403,7 +421,7 @@ losa_status losa_score_pages(losa_ctx* ctx, void* stream, const losa_kv* kv, con
   const long need = worst < msp ? worst : msp;
   if (cap < need) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap %d is below the union's worst case %ld", cap, need);
   return score_pages_impl(ctx, as_stream(stream), view_of(kv), kv->batch, msp, q, active_idx, active_count,
-                          topk_pages, topk_out, sel_pages, sel_count, cap);
+                          topk_pages, topk_out, sel_pages, sel_count, cap, /*prepare_attn=*/false);
 }
 
 losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q, const int32_t* active_idx,
@@ -420,7 +438,7 @@ losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, con
     return fail(ctx, LOSA_ERR_INVALID_ARG, "sel_pages and sel_count must both be given or both be NULL");
   if (sel_pages && cap < 1) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap must be >= 1");
   return sparse_attn_impl(ctx, as_stream(stream), view_of(kv), kv->batch, msp, q, active_idx, active_count, sel_pages,
-                          sel_count, cap, /*rows_upper=*/0, (float*)o_p, lse_p);
+                          sel_count, cap, /*rows_upper=*/0, /*prepared=*/false, (float*)o_p, lse_p);
 }
 
 losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t step_index, const void* h_cur,
@@ -436,7 +454,8 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
   hipStream_t st = as_stream(stream);
   const KvView view = view_of(kv);
   if (dense)
-    return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, nullptr, nullptr, nullptr, nullptr, 0, 0, (float*)o_p, lse_p);
+    return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, nullptr, nullptr, nullptr, nullptr, 0, 0, false,
+                            (float*)o_p, lse_p);
   if (!h_cur || !h_prev) return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_step: h_cur / h_prev are NULL");
   if (topk_pages < 1 || topk_pages > ctx->cfg.max_topk_pages)
     return fail(ctx, LOSA_ERR_INVALID_ARG, "topk_pages %d outside 1..max_topk_pages (%d)", topk_pages,
@@ -447,13 +466,14 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
                          ctx->active_count);
   if (s != LOSA_OK) return s;
   const int cap = ctx->sh.max_pages;
+  const bool fuse_prepare = ctx->cfg.dtype == LOSA_BF16;   // the selection kernel also builds the attention inputs
   s = score_pages_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, topk_pages, nullptr,
-                       ctx->sel_pages, sc, cap);
+                       ctx->sel_pages, sc, cap, fuse_prepare);
   if (s != LOSA_OK) return s;
   // the host knows |A| in the top-n modes, so the attention can be shaped for n*G rows
   const int rows_upper = mode == LOSA_SEL_THRESHOLD ? 0 : select_count(ctx, (int)mode, param) * ctx->sh.G;
   return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, ctx->sel_pages, sc,
-                          cap, rows_upper, (float*)o_p, lse_p);
+                          cap, rows_upper, fuse_prepare, (float*)o_p, lse_p);
 }
 
 }  // extern "C"

@@ -35,6 +35,15 @@ struct Partials {
   float* l;   // [items, rows_max]      sum_t exp(s_t - m)
 };
 
+// Prepared inputs of the matrix-core attention kernel, per (sequence, KV head) = `head`.
+constexpr int kEntryShift = 26;   // entry = physical page id | (valid tokens << 26)
+struct AttnPrepared {
+  int32_t* entries;   // [heads, max_pages]
+  uint16_t* q_act;    // [heads, rows_max, d] bfloat16: query rows of the active tokens, gathered
+  int32_t* ucount;    // [heads] entries in the list
+  int32_t* mrows;     // [heads] query rows (|A| * G)
+};
+
 // ---- select_active.hip
 hipError_t launch_locality_delta(hipStream_t st, int dtype, const void* h_cur, const void* h_prev,
                                  int rows, int H, float* delta);
@@ -46,28 +55,31 @@ hipError_t launch_page_bounds(hipStream_t st, int dtype, const KvView& kv, const
                               int first_page, int num_pages_in_range);
 
 // ---- score_pages.hip
+constexpr int kMaxSelectPages = 256 * 64;   // pages per sequence the register-resident top-k handles
 hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
                               const void* q, const int32_t* active_idx, const int32_t* active_count,
-                              float* scores, uint32_t* bitmap);
-hipError_t launch_topk_union(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
-                             const int32_t* active_count, const float* scores, int topk, int32_t* topk_out,
-                             uint32_t* bitmap);
-hipError_t launch_union_compact(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
-                                const int32_t* active_count, const uint32_t* bitmap,
-                                int32_t* sel_pages, int32_t* sel_count, int cap);
+                              float* scores, int32_t* tickets, int32_t* sel_count, const AttnPrepared* prep);
+hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
+                               const void* q, const int32_t* active_idx, const int32_t* active_count,
+                               const float* scores, int topk, int32_t* topk_out, int32_t* sel_pages,
+                               int32_t* sel_count, int cap, uint32_t* rowmaps, int32_t* tickets,
+                               const AttnPrepared* prep);
 
 // ---- sparse_attn.hip (element-generic kernel, merge) and sparse_attn_mfma.hip (bfloat16 matrix-core kernel)
-// Both split a (sequence, KV head) page list into `nchunk` equal shares of its actual length.
+// Both deal the 32-token tiles of a (sequence, KV head) page list round-robin to `nchunk` work items.
+// launch_attn_merge: prep != NULL means the partials came from the matrix-core kernel.
 hipError_t launch_attn_generic(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
                                const void* q, const int32_t* active_idx, const int32_t* active_count,
                                const int32_t* sel_pages, const int32_t* sel_count, int cap, int nchunk,
                                const Partials& part);
-hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
-                            const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
-                            const int32_t* sel_count, int cap, int nchunk, int rows_upper, const Partials& part);
+hipError_t launch_attn_prepare(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
+                               const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
+                               const int32_t* sel_count, int cap, const AttnPrepared& prep);
+hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
+                            int nchunk, int rows_upper, const Partials& part);
 hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch,
                              const int32_t* active_idx, const int32_t* active_count,
-                             const int32_t* sel_count, int cap, int nchunk, bool log2_units,
+                             const int32_t* sel_count, int cap, int nchunk, const AttnPrepared* prep,
                              const Partials& part, float* o_p, float* lse_p);
 
 }  // namespace losa

@@ -2,9 +2,10 @@
 // (paper: Preliminaries, Sparse Attention Algorithms for LLMs; Methodology, eq. quest_union).
 //
 //   page_scores   s[b,j,r,p] = sum_c max(q_c*min_c, q_c*max_c)   r = a*G + hg over the active slots a
-//   topk_union    per row r: exact top-K by 4-pass radix select on order-preserving keys
-//                 (ties: smaller page), bits OR-ed into the KV head's page bitmap
-//   union_compact bitmap -> ascending page list + count
+//   select_pages  per row r: exact top-K by radix select on order-preserving keys (ties:
+//                 smaller page); the last row of a KV head to finish ORs the row bitmaps,
+//                 compacts the union into an ascending page list and, inside losa_step,
+//                 also builds the attention kernel's inputs
 //
 // Everything that decides a set is integer work on float bit patterns: no float atomics,
 // so the outcome does not depend on scheduling.
@@ -13,6 +14,26 @@
 
 namespace losa {
 
+// What the scoring kernel leaves ready for the selection kernel that follows it: the ticket
+// counter of every (sequence, KV head) at zero, and - when no token is active, so that no
+// selection workgroup will run - empty results.
+struct ScoreAux {
+  int32_t* tickets;
+  int32_t* sel_count;
+  int32_t* ucount;   // nullable
+  int32_t* mrows;    // nullable
+  __device__ void reset(int head, int M) const {
+    tickets[head] = 0;
+    if (M <= 0) {
+      sel_count[head] = 0;
+      if (ucount) {
+        ucount[head] = 0;
+        mrows[head] = 0;
+      }
+    }
+  }
+};
+
 constexpr int kScorePages = 32;  // pages per workgroup in page_scores
 constexpr int kScoreRows = 32;   // query rows staged at a time
 
@@ -20,21 +41,19 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void page_scores_kernel(KvView kv, Shape sh, const T* __restrict__ q,
                                                           const int32_t* __restrict__ active_idx,
                                                           const int32_t* __restrict__ active_count,
-                                                          float* __restrict__ scores, uint32_t* __restrict__ bitmap) {
+                                                          float* __restrict__ scores, ScoreAux aux) {
   constexpr int V = Vec16<T>::n;
   constexpr int PT = kScorePages, RC = kScoreRows;
   __shared__ float mn[PT][D + 1];
   __shared__ float mx[PT][D + 1];
   __shared__ float qs[RC][D];
   const int b = blockIdx.z, j = blockIdx.y, p0 = blockIdx.x * PT, tid = threadIdx.x;
-  const int words = (sh.max_pages + 31) / 32;
-  if (blockIdx.x == 0)
-    for (int w = tid; w < words; w += 256) bitmap[((size_t)b * sh.Hkv + j) * words + w] = 0u;
   const int base = kv.page_indptr[b];
   const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
-  if (p0 >= P) return;
   const int n = min(active_count[b], sh.B);
   const int M = n * sh.G;
+  if (blockIdx.x == 0 && tid == 0) aux.reset(b * sh.Hkv + j, M);
+  if (p0 >= P) return;
   if (M <= 0) return;
 
   constexpr int VPR = D / V;  // vectors per metadata row
@@ -104,19 +123,16 @@ template <int D>
 __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape sh, const bf16_t* __restrict__ q,
                                                                const int32_t* __restrict__ active_idx,
                                                                const int32_t* __restrict__ active_count,
-                                                               float* __restrict__ scores,
-                                                               uint32_t* __restrict__ bitmap) {
+                                                               float* __restrict__ scores, ScoreAux aux) {
   constexpr int KS = D / 32;
   const int b = blockIdx.z, j = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, qd = lane >> 4;
-  const int words = (sh.max_pages + 31) / 32;
-  if (blockIdx.x == 0)
-    for (int w = tid; w < words; w += 256) bitmap[((size_t)b * sh.Hkv + j) * words + w] = 0u;
   const int base = kv.page_indptr[b];
   const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
   const int p0 = blockIdx.x * 64 + wave * 16;
-  if (p0 >= P) return;
   const int M = min(active_count[b], sh.B) * sh.G;
+  if (blockIdx.x == 0 && tid == 0) aux.reset(b * sh.Hkv + j, M);
+  if (p0 >= P) return;
   if (M <= 0) return;
 
   // A operands: metadata rows of page p0 + l16 (a valid page is read for lanes past P, never stored)
@@ -180,106 +196,79 @@ __device__ __forceinline__ uint32_t order_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-__global__ __launch_bounds__(256) void topk_union_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
-                                                         const float* __restrict__ scores, int topk,
-                                                         int32_t* __restrict__ topk_out,
-                                                         uint32_t* __restrict__ bitmap) {
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t s_bucket;
-  __shared__ int s_need;
-  __shared__ int scan[17];
-  const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
-  const int n = min(active_count[b], sh.B);
-  if (r >= n * sh.G) return;
-  const int P = min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages);
-  const int a = r / sh.G, h = j * sh.G + r % sh.G;
-  int32_t* out = topk_out ? topk_out + (((size_t)b * sh.B + a) * sh.Hq + h) * topk : nullptr;
-  const int Kp = min(topk, P);
-  const float* row = scores + (((size_t)b * sh.Hkv + j) * sh.rows_max + r) * sh.max_pages;
-  const bool all = Kp >= P;
-  uint32_t prefix = 0u, pmask = 0u;
-  int need = Kp;
-  if (!all) {
-    // K-th largest key, one byte per pass from the top
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
-      hist[tid] = 0u;
-      __syncthreads();
-      for (int p = tid; p < P; p += 256) {
-        const uint32_t key = order_key(row[p]);
-        if ((key & pmask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+// Device-wide hand-over used by the selection kernel: every row's workgroup stores its pick
+// bitmap, then takes a ticket; the workgroup that draws the last ticket of a (sequence, KV
+// head) ORs the rows, compacts the union and builds what the attention kernel consumes.
+// (How the stores are made visible to that workgroup is described at the hand-over.)
+struct SelectOut {
+  int32_t* topk_out;    // nullable [batch, B, Hq, topk]
+  int32_t* sel_pages;   // [batch, Hkv, cap] logical pages of the union, ascending
+  int32_t* sel_count;   // [batch, Hkv]
+  int cap;
+  uint32_t* rowmaps;    // workspace [heads, rows_max, words]: pick bitmap of every query row
+  int32_t* tickets;     // workspace [heads], zero on entry (zeroed by the scoring kernel), zero on exit
+  AttnPrepared prep;    // entries == NULL: do not build the attention inputs
+  const void* q;        // query tensor (for the gather into prep.q_act)
+  const int32_t* active_idx;
+};
+
+// Inclusive suffix scan over 256 histogram buckets by one wavefront: lane l owns buckets
+// 255-4l .. 252-4l (descending).  Returns through LDS the bucket where the running count from
+// the top first reaches `need`, and how many are still needed inside that bucket.
+__device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need, uint32_t* s_bucket, int* s_need) {
+  const int lane = threadIdx.x;   // caller guarantees threadIdx.x < 64
+  int c[4], tot = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    c[k] = (int)hist[255 - 4 * lane - k];
+    tot += c[k];
+  }
+  int incl = tot;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += t;
+  }
+  int above = incl - tot;   // keys in buckets owned by lower lanes (= higher buckets)
+  if (above < need && incl >= need) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (above < need && above + c[k] >= need) {
+        *s_bucket = (uint32_t)(255 - 4 * lane - k);
+        *s_need = need - above;
       }
-      __syncthreads();
-      if (tid == 0) {
-        int cum = 0, bkt = 255;
-        for (; bkt > 0; --bkt) {
-          const int c = (int)hist[bkt];
-          if (cum + c >= need) break;
-          cum += c;
-        }
-        s_bucket = (uint32_t)bkt;
-        s_need = need - cum;
-      }
-      __syncthreads();
-      prefix |= s_bucket << shift;
-      pmask |= 0xFFu << shift;
-      need = s_need;
-      __syncthreads();
+      above += c[k];
     }
   }
-  // picks in page order: every key above the K-th, plus the first `need` keys equal to it
-  const int words = (sh.max_pages + 31) / 32;
-  uint32_t* bm = bitmap + ((size_t)b * sh.Hkv + j) * words;
-  int base_sel = 0, base_eq = 0;
-  for (int p0 = 0; p0 < P; p0 += 256) {
-    const int p = p0 + tid;
-    const bool in = p < P;
-    const uint32_t key = in ? order_key(row[p]) : 0u;
-    const int gt = in && (all || key > prefix);
-    const int eq = in && !all && key == prefix;
-    int tot_eq, tot_sel;
-    const int eq_rank = base_eq + block_exclusive_scan(eq, scan, &tot_eq);
-    const int sel = gt || (eq && eq_rank < need);
-    const int pos = base_sel + block_exclusive_scan(sel, scan, &tot_sel);
-    const unsigned long long ball = __ballot(sel);
-    const int lane = tid & 63;
-    if (lane == 0 && (uint32_t)ball) atomicOr(&bm[(p0 + (tid & ~63)) / 32], (uint32_t)ball);
-    if (lane == 32 && (uint32_t)(ball >> 32)) atomicOr(&bm[(p0 + (tid & ~63)) / 32 + 1], (uint32_t)(ball >> 32));
-    if (sel && out) out[pos] = p;
-    base_eq += tot_eq;
-    base_sel += tot_sel;
-  }
-  if (out)
-    for (int k = base_sel + tid; k < topk; k += 256) out[k] = -1;
 }
 
-// Register-resident variant for P <= 256*E pages: thread t owns the E consecutive pages
-// [t*E, t*E+E), keys are read from memory once.  Per radix pass: LDS histogram of the
-// still-matching keys, then a block-wide suffix scan over the 256 buckets finds the bucket
-// holding the K-th largest key (no serial walk).  The picks of the row are assembled as a
-// bitmap in LDS and OR-ed into the KV head's bitmap one word at a time.
+// Per-query top pages by radix select, register resident (thread t owns the E consecutive
+// pages [t*E, t*E+E); P <= 256*E), fused with the union and the hand-over described above.
+// The radix starts at the highest bit in which the row's keys differ (a block min/max finds
+// it), so the first histogram is already spread over many buckets instead of piling every
+// key onto the few exponent patterns the scores share.
 template <int E>
-__global__ __launch_bounds__(256) void topk_union_reg_kernel(KvView kv, Shape sh,
-                                                             const int32_t* __restrict__ active_count,
-                                                             const float* __restrict__ scores, int topk,
-                                                             int32_t* __restrict__ topk_out,
-                                                             uint32_t* __restrict__ bitmap) {
+__global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
+                                                           const float* __restrict__ scores, int topk, SelectOut out) {
   constexpr int WORDS = 256 * E / 32;
   __shared__ uint32_t hist[256];
   __shared__ uint32_t rowbits[WORDS];
-  __shared__ uint32_t s_bucket;
-  __shared__ int s_need;
+  __shared__ uint32_t s_bucket, s_lo[4], s_hi[4];
+  __shared__ int s_need, s_last;
   __shared__ int scan[17];
   const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
-  const int n = min(active_count[b], sh.B);
-  if (r >= n * sh.G) return;
-  const int P = min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages);
-  if (P <= 0) return;
+  const int head = b * sh.Hkv + j;
+  const int n_act = min(active_count[b], sh.B);
+  const int M = n_act * sh.G;
+  if (r >= M) return;
+  const int P = max(0, min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages));
+  const int words = (sh.max_pages + 31) / 32;
   const int a = r / sh.G, h = j * sh.G + r % sh.G;
-  int32_t* out = topk_out ? topk_out + (((size_t)b * sh.B + a) * sh.Hq + h) * topk : nullptr;
+  int32_t* tk = out.topk_out ? out.topk_out + (((size_t)b * sh.B + a) * sh.Hq + h) * topk : nullptr;
   const int Kp = min(topk, P);
-  const float* row = scores + (((size_t)b * sh.Hkv + j) * sh.rows_max + r) * sh.max_pages;
+  const float* row = scores + ((size_t)head * sh.rows_max + r) * sh.max_pages;
   const int p_first = tid * E;
+  const int nmine = max(0, min(E, P - p_first));   // pages of this thread that exist
 
   uint32_t key[E];
   if (p_first + E <= P && (sh.max_pages & 3) == 0) {
@@ -293,35 +282,80 @@ __global__ __launch_bounds__(256) void topk_union_reg_kernel(KvView kv, Shape sh
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < E; ++i) key[i] = p_first + i < P ? order_key(row[p_first + i]) : 0u;
+    for (int i = 0; i < E; ++i) key[i] = i < nmine ? order_key(row[p_first + i]) : 0u;
   }
-  const int nmine = max(0, min(E, P - p_first));   // pages of this thread that exist
-
   for (int w = tid; w < WORDS; w += 256) rowbits[w] = 0u;
+
+  // Row 0 of every (sequence, head) also gathers the head's active query rows into the dense
+  // buffer the attention kernel reads; the loads are issued here and stored after the select,
+  // so the gather rides along with the radix passes instead of following them.
+  constexpr int QV = 4;                       // 16-byte vectors per thread per sweep
+  const bool gather = out.prep.entries != nullptr && r == 0;
+  const int vpr = sh.d / 8;
+  uint4 qv[QV];
+  if (gather) {
+    const bf16_t* q = (const bf16_t*)out.q;
+#pragma unroll
+    for (int k = 0; k < QV; ++k) {
+      const int v = tid + 256 * k;
+      qv[k] = make_uint4(0u, 0u, 0u, 0u);
+      if (v < M * vpr) {
+        const int rr = v / vpr, cv = v % vpr;
+        const int tok = out.active_idx[(size_t)b * sh.B + rr / sh.G];
+        if ((unsigned)tok < (unsigned)sh.B)
+          qv[k] = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + rr % sh.G) * sh.d)[cv];
+      }
+    }
+  }
+
   const bool all = Kp >= P;
   uint32_t prefix = 0u, pmask = 0u;
   int need = Kp;
   if (!all) {
-    for (int pass = 0; pass < 4; ++pass) {
-      const int shift = 24 - 8 * pass;
-      hist[tid] = 0u;
-      __syncthreads();
+    // highest differing bit of the row's keys
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
 #pragma unroll
-      for (int i = 0; i < E; ++i)
-        if (i < nmine && (key[i] & pmask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1u);
-      __syncthreads();
-      // thread t looks at bucket 255-t: its inclusive prefix over t is the count of keys in buckets >= 255-t
-      const int c = (int)hist[255 - tid];
-      int total;
-      const int above = block_exclusive_scan(c, scan, &total);   // keys in strictly higher buckets
-      if (above < need && above + c >= need) {
-        s_bucket = (uint32_t)(255 - tid);
-        s_need = need - above;
+    for (int i = 0; i < E; ++i)
+      if (i < nmine) {
+        lo = min(lo, key[i]);
+        hi = max(hi, key[i]);
       }
-      __syncthreads();
-      prefix |= s_bucket << shift;
-      pmask |= 0xFFu << shift;
-      need = s_need;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      lo = min(lo, (uint32_t)__shfl_xor((int)lo, o, 64));
+      hi = max(hi, (uint32_t)__shfl_xor((int)hi, o, 64));
+    }
+    if ((tid & 63) == 0) {
+      s_lo[tid >> 6] = lo;
+      s_hi[tid >> 6] = hi;
+    }
+    __syncthreads();
+    lo = min(min(s_lo[0], s_lo[1]), min(s_lo[2], s_lo[3]));
+    hi = max(max(s_hi[0], s_hi[1]), max(s_hi[2], s_hi[3]));
+    const uint32_t diff = lo ^ hi;
+    if (diff != 0u) {
+      const int hb = 31 - __clz((int)diff);          // keys agree above bit hb
+      pmask = hb >= 31 ? 0u : ~((2u << hb) - 1u);
+      prefix = hi & pmask;
+      for (int shift = max(hb - 7, 0);; shift = max(shift - 8, 0)) {
+        hist[tid] = 0u;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < E; ++i)
+          if (i < nmine && (key[i] & pmask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1u);
+        __syncthreads();
+        if (tid < 64) find_bucket_wave0(hist, need, &s_bucket, &s_need);
+        __syncthreads();
+        // bits of the digit that lie above bit hb (only when hb < 7) are common to all keys
+        const uint32_t dmask = 0xFFu << shift;
+        prefix = (prefix & ~dmask) | (s_bucket << shift);
+        pmask |= dmask;
+        need = s_need;
+        if (shift == 0) break;
+      }
+    } else {
+      prefix = hi;          // every key is the same: ties by page order
+      pmask = 0xFFFFFFFFu;
     }
   } else {
     __syncthreads();
@@ -334,10 +368,10 @@ __global__ __launch_bounds__(256) void topk_union_reg_kernel(KvView kv, Shape sh
     my_gt += in && (all || key[i] > prefix);
     my_eq += in && !all && key[i] == prefix;
   }
-  int tot_eq, tot_sel;
+  int tot_eq;
   int eq_rank = block_exclusive_scan(my_eq, scan, &tot_eq);
-  int my_sel = my_gt + max(0, min(my_eq, need - eq_rank));
-  int pos = block_exclusive_scan(my_sel, scan, &tot_sel);
+  int pos = 0, tot_sel = 0;
+  if (tk) pos = block_exclusive_scan(my_gt + max(0, min(my_eq, need - eq_rank)), scan, &tot_sel);
   uint32_t bits[(E + 31) / 32];
 #pragma unroll
   for (int w = 0; w < (E + 31) / 32; ++w) bits[w] = 0u;
@@ -351,97 +385,180 @@ __global__ __launch_bounds__(256) void topk_union_reg_kernel(KvView kv, Shape sh
     }
     if (sel) {
       bits[i / 32] |= 1u << ((p_first + i) & 31);
-      if (out) out[pos] = p_first + i;
-      ++pos;
+      if (tk) tk[pos++] = p_first + i;
     }
   }
   if (E >= 32) {
 #pragma unroll
-    for (int w = 0; w < (E + 31) / 32; ++w)
-      if (bits[w]) rowbits[p_first / 32 + w] = bits[w];   // this thread owns whole words
+    for (int w = 0; w < (E + 31) / 32; ++w) rowbits[p_first / 32 + w] = bits[w];   // this thread owns whole words
   } else {
     if (bits[0]) atomicOr(&rowbits[p_first / 32], bits[0]);
   }
+  if (tk)
+    for (int k = tot_sel + tid; k < topk; k += 256) tk[k] = -1;
   __syncthreads();
-  const int words = (sh.max_pages + 31) / 32;
-  uint32_t* bm = bitmap + ((size_t)b * sh.Hkv + j) * words;
-  for (int w = tid; w < WORDS && w < words; w += 256)
-    if (rowbits[w]) atomicOr(&bm[w], rowbits[w]);
-  if (out)
-    for (int k = tot_sel + tid; k < topk; k += 256) out[k] = -1;
-}
-
-__global__ __launch_bounds__(256) void union_compact_kernel(KvView kv, Shape sh, const uint32_t* __restrict__ bitmap,
-                                                            int32_t* __restrict__ sel_pages,
-                                                            int32_t* __restrict__ sel_count, int cap) {
-  __shared__ int scan[17];
-  const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
-  const int P = kv.page_indptr[b + 1] - kv.page_indptr[b];
-  const int words = (sh.max_pages + 31) / 32, wordsP = (min(P, sh.max_pages) + 31) / 32;
-  const uint32_t* bm = bitmap + ((size_t)b * sh.Hkv + j) * words;
-  int32_t* out = sel_pages + ((size_t)b * sh.Hkv + j) * cap;
-  int base_out = 0;
-  for (int w0 = 0; w0 < wordsP; w0 += 256) {
-    const int w = w0 + tid;
-    uint32_t bits = w < wordsP ? bm[w] : 0u;
-    int total;
-    int pos = base_out + block_exclusive_scan(__popc(bits), scan, &total);
-    while (bits) {
-      const int bit = __ffs((int)bits) - 1;
-      if (pos < cap) out[pos] = w * 32 + bit;
-      ++pos;
-      bits &= bits - 1u;
+  if (gather) {
+    const bf16_t* q = (const bf16_t*)out.q;
+    uint4* dst = reinterpret_cast<uint4*>(out.prep.q_act + (size_t)head * sh.rows_max * sh.d);
+#pragma unroll
+    for (int k = 0; k < QV; ++k)
+      if (tid + 256 * k < M * vpr) dst[tid + 256 * k] = qv[k];
+    for (int v = tid + 256 * QV; v < M * vpr; v += 256) {   // more than QV*256 vectors: the rest, plainly
+      const int rr = v / vpr, cv = v % vpr;
+      const int tok = out.active_idx[(size_t)b * sh.B + rr / sh.G];
+      uint4 val = make_uint4(0u, 0u, 0u, 0u);
+      if ((unsigned)tok < (unsigned)sh.B)
+        val = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + rr % sh.G) * sh.d)[cv];
+      dst[v] = val;
     }
+  }
+
+  // ---- hand-over: the last row of this (sequence, head) builds the union.
+  // The row bitmap travels in agent-scope atomic stores (written through to memory, past the
+  // per-die L2 slices); ordering is "my stores have completed (wait count zero), then my
+  // ticket".  A full agent-scope fence would also work but writes back and invalidates whole
+  // L2 slices, once per workgroup.
+  uint32_t* myrow = out.rowmaps + ((size_t)head * sh.rows_max + r) * words;
+  for (int w = tid; w < words; w += 256)
+    __hip_atomic_store(&myrow[w], w < WORDS ? rowbits[w] : 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __builtin_amdgcn_s_waitcnt(0);
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
+  __syncthreads();
+  if (tid == 0) s_last = __hip_atomic_fetch_add(&out.tickets[head], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == M - 1;
+  __syncthreads();
+  if (!s_last) return;
+  if (tid == 0) out.tickets[head] = 0;
+  // Union of the M row bitmaps -> ascending page list (+ page entries for the attention kernel).
+  // Pages are handled a thread each, kTailPages per thread: their physical ids are fetched
+  // before the bits are known, together with the row bitmaps, so the tail is one memory
+  // round trip.  A page's slot in the list is the popcount prefix of its bitmap word plus
+  // the set bits below it in the word: no serial walk, stores ascend with the thread id.
+  const int wordsP = (P + 31) / 32;
+  int32_t* sel = out.sel_pages + (size_t)head * out.cap;
+  const int base = kv.page_indptr[b];
+  const int L = kv.seq_lens[b];
+  int32_t* ent = out.prep.entries ? out.prep.entries + (size_t)head * sh.max_pages : nullptr;
+  __shared__ int wordbase[WORDS];
+  for (int w = tid; w < WORDS; w += 256) rowbits[w] = 0u;
+  int phys[E];
+  if (ent) {
+#pragma unroll
+    for (int i = 0; i < E; ++i) phys[i] = kv.page_indices[base + min(tid + 256 * i, max(P - 1, 0))];
+  }
+  __syncthreads();
+  const uint32_t* maps = out.rowmaps + (size_t)head * sh.rows_max * words;
+  {
+    // 16 independent loads at a time (a loop of load-then-use would pay one memory latency per
+    // iteration).  Plain loads: they cannot see stale data, since each cache line of the row
+    // bitmaps has exactly one writer in this launch and no reader before this point, the
+    // caches were invalidated when the launch began, and the writer's stores went through to
+    // memory (agent scope) before its ticket was drawn.
+    const int count = M * wordsP;
+    for (int i0 = tid; i0 < count; i0 += 256 * 16) {
+      uint32_t v[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        const int idx = i0 + 256 * k;
+        const int rr = idx / wordsP, ww = idx - rr * wordsP;
+        v[k] = idx < count ? maps[(size_t)rr * words + ww] : 0u;
+      }
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        const int idx = i0 + 256 * k;
+        const int rr = idx / wordsP, ww = idx - rr * wordsP;
+        if (v[k]) atomicOr(&rowbits[ww], v[k]);
+      }
+    }
+  }
+  __syncthreads();
+  int base_out = 0;
+  for (int w0 = 0; w0 < WORDS; w0 += 256) {   // exclusive popcount prefix per word
+    const int w = w0 + tid;
+    const int c = w < wordsP ? __popc(rowbits[w]) : 0;
+    int total;
+    const int ex = block_exclusive_scan(c, scan, &total);
+    if (w < WORDS) wordbase[w] = base_out + ex;
     base_out += total;
   }
-  if (tid == 0) sel_count[b * sh.Hkv + j] = min(base_out, cap);
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const int page = tid + 256 * i;
+    if (page < P) {
+      const uint32_t word = rowbits[page >> 5];
+      if ((word >> (page & 31)) & 1u) {
+        const int at = wordbase[page >> 5] + __popc(word & ((1u << (page & 31)) - 1u));
+        if (at < out.cap) {
+          sel[at] = page;
+          if (ent) {
+            const int nv = max(0, min(sh.g, L - page * sh.g));
+            const int ph = phys[i];
+            ent[at] = ((unsigned)ph < (unsigned)kv.num_pages && ph < (1 << kEntryShift)) ? (ph | (nv << kEntryShift)) : 0;
+          }
+        }
+      }
+    }
+  }
+  const int U = min(base_out, out.cap);
+  if (tid == 0) {
+    out.sel_count[head] = U;
+    if (ent) {
+      out.prep.ucount[head] = U;
+      out.prep.mrows[head] = M;
+    }
+  }
 }
 
 hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
                               int max_seq_pages, const void* q, const int32_t* active_idx,
-                              const int32_t* active_count, float* scores, uint32_t* bitmap) {
+                              const int32_t* active_count, float* scores, int32_t* tickets, int32_t* sel_count,
+                              const AttnPrepared* prep) {
   if (batch <= 0) return hipSuccess;
+  ScoreAux aux{tickets, sel_count, prep ? prep->ucount : nullptr, prep ? prep->mrows : nullptr};
   dim3 grid((max_seq_pages + kScorePages - 1) / kScorePages, sh.Hkv, batch);
   if (grid.x == 0) grid.x = 1;
   if (dtype == LOSA_BF16) {
     dim3 mgrid((max_seq_pages + 63) / 64, sh.Hkv, batch);
     if (mgrid.x == 0) mgrid.x = 1;
     if (sh.d == 128)
-      page_scores_mfma_kernel<128><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, bitmap);
+      page_scores_mfma_kernel<128><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux);
     else
-      page_scores_mfma_kernel<64><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, bitmap);
+      page_scores_mfma_kernel<64><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux);
   } else {
     if (sh.d == 128)
-      page_scores_kernel<float, 128><<<grid, 256, 0, st>>>(kv, sh, (const float*)q, active_idx, active_count, scores, bitmap);
+      page_scores_kernel<float, 128><<<grid, 256, 0, st>>>(kv, sh, (const float*)q, active_idx, active_count, scores, aux);
     else
-      page_scores_kernel<float, 64><<<grid, 256, 0, st>>>(kv, sh, (const float*)q, active_idx, active_count, scores, bitmap);
+      page_scores_kernel<float, 64><<<grid, 256, 0, st>>>(kv, sh, (const float*)q, active_idx, active_count, scores, aux);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_topk_union(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
-                             const int32_t* active_count, const float* scores, int topk, int32_t* topk_out,
-                             uint32_t* bitmap) {
+hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
+                               const void* q, const int32_t* active_idx, const int32_t* active_count,
+                               const float* scores, int topk, int32_t* topk_out, int32_t* sel_pages,
+                               int32_t* sel_count, int cap, uint32_t* rowmaps, int32_t* tickets,
+                               const AttnPrepared* prep) {
   if (batch <= 0) return hipSuccess;
+  SelectOut out;
+  out.topk_out = topk_out;
+  out.sel_pages = sel_pages;
+  out.sel_count = sel_count;
+  out.cap = cap;
+  out.rowmaps = rowmaps;
+  out.tickets = tickets;
+  out.prep = prep ? *prep : AttnPrepared{nullptr, nullptr, nullptr, nullptr};
+  out.q = q;
+  out.active_idx = active_idx;
   dim3 grid(sh.rows_max, sh.Hkv, batch);
   const int pages = max_seq_pages < sh.max_pages ? max_seq_pages : sh.max_pages;
   if (pages <= 256 * 8)
-    topk_union_reg_kernel<8><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, topk_out, bitmap);
+    select_pages_kernel<8><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
   else if (pages <= 256 * 32)
-    topk_union_reg_kernel<32><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, topk_out, bitmap);
+    select_pages_kernel<32><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
+  else if (pages <= kMaxSelectPages)
+    select_pages_kernel<64><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
   else
-    topk_union_kernel<<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, topk_out, bitmap);
-  return hipGetLastError();
-}
-
-hipError_t launch_union_compact(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
-                                const int32_t* active_count, const uint32_t* bitmap, int32_t* sel_pages,
-                                int32_t* sel_count, int cap) {
-  (void)max_seq_pages;
-  (void)active_count;
-  if (batch <= 0) return hipSuccess;
-  dim3 grid(sh.Hkv, batch);
-  union_compact_kernel<<<grid, 256, 0, st>>>(kv, sh, bitmap, sel_pages, sel_count, cap);
+    return hipErrorInvalidValue;
   return hipGetLastError();
 }
 

@@ -56,10 +56,8 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
   const int32_t* list = sel_pages ? sel_pages + ((size_t)b * sh.Hkv + j) * cap : nullptr;
   const int U = list ? min(sel_count[b * sh.Hkv + j], cap) : P;
   const int ntiles = (U + PPT - 1) / PPT;
-  const int tpc = (ntiles + nchunk - 1) / nchunk;   // tiles per chunk: equal shares of the real list
-  const int tile0 = chunk * tpc, tile1 = min(ntiles, tile0 + tpc);
-  if (tile0 >= tile1) return;
-  const int c0 = tile0 * PPT, c1 = min(U, tile1 * PPT);
+  if (chunk >= ntiles) return;   // tiles are dealt round-robin: chunk, chunk + nchunk, ...
+  const int c1 = U;
 
   for (int v = tid; v < kRowBlock * VPR; v += 256) {
     const int rr = v / VPR, cv = v % VPR, r = r0 + rr;
@@ -85,7 +83,8 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
 #pragma unroll
   for (int k = 0; k < CPT; ++k) acc[k] = 0;
 
-  for (int pp = c0; pp < c1; pp += PPT) {
+  for (int tile = chunk; tile < ntiles; tile += nchunk) {
+    const int pp = tile * PPT;
     __syncthreads();
     // ---- stage one tile of keys (token-major pages) and values (channel-major pages)
     for (int v = tid; v < kTileTok * VPR; v += 256) {
@@ -203,25 +202,31 @@ template <int D, bool LOG2>
 __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_idx,
                                                          const int32_t* __restrict__ active_count,
                                                          const int32_t* __restrict__ sel_count, int cap, int nchunk,
-                                                         Partials part, float* __restrict__ o_p,
-                                                         float* __restrict__ lse_p) {
+                                                         const int32_t* __restrict__ ucount,
+                                                         const int32_t* __restrict__ mrows, Partials part,
+                                                         float* __restrict__ o_p, float* __restrict__ lse_p) {
   typedef typename std::conditional<LOG2, float, double>::type Acc;
   constexpr int C4 = D / 4, CL = 256 / C4;
   __shared__ Acc red[CL][D];
   __shared__ Acc lred[CL];
   __shared__ float wmax[4];
   const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
-  const int n = active_idx ? min(active_count[b], sh.B) : sh.B;
-  if (r >= n * sh.G) return;
+  int M, U;
+  if (ucount) {   // prepared by the matrix-core path
+    M = min(mrows[b * sh.Hkv + j], sh.rows_max);
+    U = min(ucount[b * sh.Hkv + j], sh.max_pages);
+  } else {
+    M = (active_idx ? min(active_count[b], sh.B) : sh.B) * sh.G;
+    const int P = min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages);
+    U = sel_count ? min(sel_count[b * sh.Hkv + j], cap) : P;
+  }
+  if (r >= M) return;
   const int a = r / sh.G, hg = r % sh.G;
   const int tok = active_idx ? active_idx[(size_t)b * sh.B + a] : a;
   if ((unsigned)tok >= (unsigned)sh.B) return;
-  const int P = min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages);
-  const int U = sel_count ? min(sel_count[b * sh.Hkv + j], cap) : P;
   const int ppt = 32 / sh.g;
   const int ntiles = (U + ppt - 1) / ppt;
-  const int tpc = (ntiles + nchunk - 1) / nchunk;
-  const int live = ntiles > 0 ? (ntiles + tpc - 1) / tpc : 0;
+  const int live = min(nchunk, ntiles);   // work item c exists iff tile c does
   const size_t item0 = ((size_t)b * sh.Hkv + j) * nchunk;
 
   float mx = -INFINITY;
@@ -300,19 +305,21 @@ hipError_t launch_attn_generic(hipStream_t st, int dtype, const KvView& kv, cons
 
 hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const int32_t* active_idx,
                              const int32_t* active_count, const int32_t* sel_count, int cap, int nchunk,
-                             bool log2_units, const Partials& part, float* o_p, float* lse_p) {
+                             const AttnPrepared* prep, const Partials& part, float* o_p, float* lse_p) {
   if (batch <= 0) return hipSuccess;
   dim3 grid(sh.rows_max, sh.Hkv, batch);
+  const int32_t* uc = prep ? prep->ucount : nullptr;
+  const int32_t* mr = prep ? prep->mrows : nullptr;
   if (sh.d == 128) {
-    if (log2_units)
-      attn_merge_kernel<128, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, part, o_p, lse_p);
+    if (prep)
+      attn_merge_kernel<128, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p);
     else
-      attn_merge_kernel<128, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, part, o_p, lse_p);
+      attn_merge_kernel<128, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p);
   } else {
-    if (log2_units)
-      attn_merge_kernel<64, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, part, o_p, lse_p);
+    if (prep)
+      attn_merge_kernel<64, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p);
     else
-      attn_merge_kernel<64, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, part, o_p, lse_p);
+      attn_merge_kernel<64, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p);
   }
   return hipGetLastError();
 }

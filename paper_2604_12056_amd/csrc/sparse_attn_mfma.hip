@@ -8,26 +8,27 @@
 //                           token-major key page (each lane one 16-byte load);
 //                           B operand = the query fragment, resident in registers.
 //   O^T += V_tile^T . P^T   A operand = 16 channels x 32 tokens, read straight from the
-//                           channel-major value page (two 8-byte loads per lane);
+//                           channel-major value page (one 16-byte load per lane);
 //                           B operand = P^T, which is exactly how S^T leaves the matrix core
 //                           (lane = query column, 4+4 tokens), so probabilities never cross
 //                           lanes and the per-row rescale factor is lane-local as well.
 //
-// The k-index of the second product is a permutation of the 32 tokens of a tile (slot e<4:
-// token 4*(lane/16)+e of the first 16-token half, slot e>=4: the same of the second half);
-// both operands use it, which is all a contraction needs.
+// The 16 rows of a score-product half are a chosen subset of the tile's 32 tokens such that
+// each lane ends up with 8 consecutive tokens; both operands of the second product use that
+// same token order, which is all a contraction needs.
 //
-// No LDS and no barrier in the main loop: K/V go global -> registers in operand layout, one
-// tile ahead.  Two work shapes:
-//   split-pages (rows <= 64): the four wavefronts of a workgroup take interleaved tiles of
-//       the same chunk and combine their (max, sum, O) through LDS at the end, so one
-//       partial leaves the workgroup;
+// No LDS and no barrier in the main loop: K/V go global -> registers in operand layout,
+// several tiles ahead.  Two work shapes:
+//   split-pages (rows <= 64): the four wavefronts of a workgroup take interleaved tiles and
+//       combine their (reference, sum, O) through LDS at the end, so one partial leaves
+//       the workgroup;
 //   split-rows (rows > 64, e.g. the dense initialisation): the four wavefronts take four
 //       64-row blocks and all walk the same tiles (served by the CU's L1 after the first).
-// Chunks are equal shares of the *actual* list length read from device memory, so every
-// workgroup of a (sequence, head) gets the same number of tiles whatever the union size is.
+// Tiles of a (sequence, head) list are dealt round-robin to its workgroups, so every
+// workgroup gets the same number of tiles (within one) whatever the union size turns out to be.
 #include <math.h>
 
+#include "attn_prepare.h"
 #include "losa_device.h"
 #include "losa_internal.h"
 
@@ -41,22 +42,58 @@ constexpr float kNegBig = -1.0e30f;   // finite stand-in for "no token seen yet"
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Plain hardware max (no NaN canonicalisation of the inputs: scores are finite or -inf here).
+__device__ __forceinline__ float vmax(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float vmax3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+// max over the 4 lanes {l, l^16, l^32, l^48} with the gfx950 lane-swap instructions (vector ALU,
+// no LDS round trip): after a swap of a register with itself the pair holds both halves.
+__device__ __forceinline__ float max_over_lane_groups(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float m16 = vmax(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const unsigned w = __float_as_uint(m16);
+  const auto c = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return vmax(__uint_as_float(c[0]), __uint_as_float(c[1]));
+}
+__device__ __forceinline__ float sum_over_lane_groups(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float s16 = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const unsigned w = __float_as_uint(s16);
+  const auto c = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return __uint_as_float(c[0]) + __uint_as_float(c[1]);
+}
+
 template <int D, int R>
 struct MergeSlot {   // LDS image of one wavefront's state
   static constexpr int kStride = D + 4;   // +4 floats: 16-byte row writes of 16 lanes land on distinct banks
   static constexpr int kFloats = R * 16 * (kStride + 2);
 };
 
-template <int D, int GP, int R, bool SPLIT_PAGES>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, const bf16_t* __restrict__ q,
-                                                        const int32_t* __restrict__ active_idx,
-                                                        const int32_t* __restrict__ active_count,
-                                                        const int32_t* __restrict__ sel_pages,
-                                                        const int32_t* __restrict__ sel_count, int cap, int nchunk,
-                                                        int nrbg, Partials part, float scale_log2e) {
+// Inputs of the matrix-core kernel are *prepared* per (sequence, KV head) by whoever decided
+// the selection (the union kernel inside losa_step, or attn_prepare_kernel for the
+// stand-alone entry point and the dense initialisation):
+//   entries[i] = physical page id | (valid tokens << kEntryShift)   for the i-th page of the list
+//   q_act      = the query rows of the active tokens, gathered densely, [rows_max, d] bfloat16
+//   ucount     = number of list entries,  mrows = number of query rows (|A| * G)
+// so that a wavefront can issue its page-entry loads, its query loads and the two counts all
+// at once when it starts: the only dependent memory round trip left before key/value data
+// flows is entries -> pages.
+template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, AttnPrepared prep, int nchunk, int nrbg,
+                                                        Partials part, float scale_log2e) {
   constexpr int KS = D / 32;    // k-steps of the score product
   constexpr int NT = D / 16;    // channel tiles of the output
   constexpr int PPT = 32 / GP;  // pages per 32-token tile
+  constexpr int TPR = 64 / PPT; // tiles covered by one page-entry fetch (one entry per lane)
   extern __shared__ float lds[];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -64,45 +101,50 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, con
   const int chunk = blockIdx.x, b = blockIdx.z;
   const int j = SPLIT_PAGES ? blockIdx.y : blockIdx.y / nrbg;
   const int rb = SPLIT_PAGES ? 0 : (blockIdx.y % nrbg) * 4 + wave;
+  const int head = b * sh.Hkv + j;
 
-  const int n_act = active_idx ? min(active_count[b], sh.B) : sh.B;
-  const int M = n_act * sh.G;
-  if (M <= 0) return;
-  if (!SPLIT_PAGES && rb * (R * 16) >= M) return;   // no barrier is used in this shape
-
-  const int base = kv.page_indptr[b];
-  const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
-  const int L = kv.seq_lens[b];
-  const int32_t* list = sel_pages ? sel_pages + ((size_t)b * sh.Hkv + j) * cap : nullptr;
-  const int U = list ? min(sel_count[b * sh.Hkv + j], cap) : P;
-  const int ntiles = (U + PPT - 1) / PPT;
-  const int tpc = (ntiles + nchunk - 1) / nchunk;   // tiles per chunk: equal shares of the real list
-  const int tile0 = chunk * tpc;
-  const int tile1 = min(ntiles, tile0 + tpc);
-  if (tile0 >= tile1) return;
-
+  // Tiles are dealt round-robin: workgroup `chunk` owns tiles chunk, chunk+nchunk, ... of the
+  // list, and in the split-pages shape its four wavefronts deal those out again.  Which tiles
+  // a wavefront owns therefore does not depend on the list length, only whether they exist.
   const int wstart = SPLIT_PAGES ? wave : 0, wstride = SPLIT_PAGES ? 4 : 1;
-  const int wfirst = tile0 + wstart;
-  const int ntw = wfirst < tile1 ? (tile1 - wfirst + wstride - 1) / wstride : 0;   // this wavefront's tiles
+  const int tfirst = chunk + nchunk * wstart;   // first tile of this wavefront
+  const int tstep = nchunk * wstride;           // distance between its tiles
+  const int32_t* ent = prep.entries + (size_t)head * sh.max_pages;
 
-  // ---- query fragments (B operand of the score product), zero for rows past M
+  // ---- everything below is issued before anything is waited for
+  const int U = min(prep.ucount[head], sh.max_pages);
+  const int M = min(prep.mrows[head], sh.rows_max);
+  int pg_entry;
+  auto fetch_entries = [&](int first_local_tile) {
+    const long lp = ((long)tfirst + (long)(first_local_tile + lane / PPT) * tstep) * PPT + lane % PPT;
+    pg_entry = lp < sh.max_pages ? ent[lp] : 0;   // inside the array whatever U is; checked against U at use
+  };
+  fetch_entries(0);
   bf16x8_t qf[R][KS];
+  {
+    const bf16_t* qa = prep.q_act + (size_t)head * sh.rows_max * D;
 #pragma unroll
-  for (int mt = 0; mt < R; ++mt) {
-    const int rg = rb * (R * 16) + mt * 16 + l16;
-    const bf16_t* qrow = nullptr;
-    if (rg < M) {
-      const int a = rg / sh.G, hg = rg % sh.G;
-      const int tok = active_idx ? active_idx[(size_t)b * sh.B + a] : a;
-      if ((unsigned)tok < (unsigned)sh.B) qrow = q + (((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + hg) * D;
-    }
+    for (int mt = 0; mt < R; ++mt) {
+      const int rg = min(rb * (R * 16) + mt * 16 + l16, sh.rows_max - 1);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-      if (qrow) raw = *reinterpret_cast<const uint4*>(qrow + ks * 32 + qd * 8);
-      qf[mt][ks] = __builtin_bit_cast(bf16x8_t, raw);
+      for (int ks = 0; ks < KS; ++ks)
+        qf[mt][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qa + (size_t)rg * D + ks * 32 + qd * 8));
     }
   }
+
+  if (M <= 0) return;
+  if (!SPLIT_PAGES && rb * (R * 16) >= M) return;   // no barrier is used in this shape
+  const int ntiles = (U + PPT - 1) / PPT;
+  if (chunk >= ntiles) return;                      // this workgroup owns no tile
+  const int ntw = tfirst < ntiles ? (ntiles - 1 - tfirst) / tstep + 1 : 0;   // this wavefront's tiles
+
+  // rows past M hold whatever the workspace held: make them zero queries
+#pragma unroll
+  for (int mt = 0; mt < R; ++mt)
+    if (rb * (R * 16) + mt * 16 + l16 >= M) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) qf[mt][ks] = __builtin_bit_cast(bf16x8_t, make_uint4(0u, 0u, 0u, 0u));
+    }
 
   float m_run[R], l_run[R];
   f32x4_t o[R][NT];
@@ -114,164 +156,219 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, con
     for (int nt = 0; nt < NT; ++nt) o[mt][nt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
   }
 
-  // ---- page ids of this wavefront's next 64 pages, one per lane (refilled every 64/PPT tiles)
+  // ---- decoded page entries of this wavefront's next 64 pages, one per lane
   int pg_phys = 0, pg_valid = 0;
-  auto fetch_pages = [&](int first_local_tile) {
-    const int n = first_local_tile + lane / PPT;
-    const int lp = (wfirst + n * wstride) * PPT + lane % PPT;
-    int phys = 0, valid = 0;
-    if (n < ntw && lp < U) {
-      const int logical = list ? list[lp] : lp;
-      if ((unsigned)logical < (unsigned)P) {
-        const int ph = kv.page_indices[base + logical];
-        if ((unsigned)ph < (unsigned)kv.num_pages) {
-          phys = ph;
-          valid = max(0, min(GP, L - logical * GP));
-        }
-      }
-    }
-    pg_phys = phys;
-    pg_valid = valid;
+  auto decode_entries = [&](int first_local_tile) {
+    const long lp = ((long)tfirst + (long)(first_local_tile + lane / PPT) * tstep) * PPT + lane % PPT;
+    const int e = lp < U ? pg_entry : 0;
+    const int ph = e & ((1 << kEntryShift) - 1);
+    const bool ok = (unsigned)ph < (unsigned)kv.num_pages;
+    pg_phys = ok ? ph : 0;
+    pg_valid = ok ? min(GP, (int)((unsigned)e >> kEntryShift)) : 0;
   };
 
+  // A 32-token tile is fed to the matrix core as two 16-row halves.  Row i of half h is token
+  //   tt(h, i) = 8*(i/4) + 4*h + (i%4)
+  // of the tile, so that after the score product lane group qd holds tokens 8*qd .. 8*qd+7
+  // (half 0 gives +0..3, half 1 gives +4..7): the 8 k-slots of the second product are 8
+  // CONSECUTIVE tokens and its value operand is one 16-byte load from the channel-major page.
   struct Tile {
     bf16x8_t k[2][KS];
-    uint2 v[NT][2];
-    int nv[2];
+    uint4 v[NT];
+    int nv[2];   // GP == 16: valid tokens of the tile's two pages; GP == 32: {min(nv,16), max(nv-16,0)}
   };
 
-  auto load_tile = [&](Tile& t, int n) {
+  // n >= ne asks for a tile that does not exist: the same number of loads is issued (so the
+  // count of loads in flight stays a compile-time constant), but all lanes read the first few
+  // lines of the pool, which costs a handful of cache hits instead of a tile of traffic.
+  auto load_tile = [&](Tile& t, int n, int ne) {
+    const bool real = n < ne;
     const int slot = (n * PPT) & 63;
-    const bf16_t *kA, *kB, *vA, *vB;
+    const bf16_t *k0, *k1, *vp;
     if (GP == 16) {
-      const int pa = __builtin_amdgcn_readlane(pg_phys, slot), pb = __builtin_amdgcn_readlane(pg_phys, slot + 1);
-      t.nv[0] = __builtin_amdgcn_readlane(pg_valid, slot);
-      t.nv[1] = __builtin_amdgcn_readlane(pg_valid, slot + 1);
-      const size_t ta = (size_t)pa * sh.Hkv + j, tb = (size_t)pb * sh.Hkv + j;
-      kA = (const bf16_t*)kv.k_pages + ta * (GP * D);
-      kB = (const bf16_t*)kv.k_pages + tb * (GP * D);
-      vA = (const bf16_t*)kv.v_pages + ta * (GP * D);
-      vB = (const bf16_t*)kv.v_pages + tb * (GP * D);
+      const int pa = real ? __builtin_amdgcn_readlane(pg_phys, slot) : 0;
+      const int pb = real ? __builtin_amdgcn_readlane(pg_phys, slot + 1) : 0;
+      t.nv[0] = real ? __builtin_amdgcn_readlane(pg_valid, slot) : 0;
+      t.nv[1] = real ? __builtin_amdgcn_readlane(pg_valid, slot + 1) : 0;
+      // lanes l16 < 8 read rows of the first page, the others of the second; row within the page:
+      // half 0 -> {0..3, 8..11}, half 1 -> {4..7, 12..15}
+      const size_t tk = (size_t)(l16 < 8 ? pa : pb) * sh.Hkv + j;
+      const int row0 = real ? 8 * ((l16 >> 2) & 1) + (l16 & 3) : 0;
+      k0 = (const bf16_t*)kv.k_pages + tk * (GP * D) + row0 * D;
+      k1 = k0 + (real ? 4 * D : 0);
+      const size_t tv = (size_t)(qd < 2 ? pa : pb) * sh.Hkv + j;
+      vp = (const bf16_t*)kv.v_pages + tv * (GP * D) + (real ? l16 * GP : 0) + 8 * (qd & 1);
     } else {
-      const int pa = __builtin_amdgcn_readlane(pg_phys, slot);
-      const int nv = __builtin_amdgcn_readlane(pg_valid, slot);
-      t.nv[0] = min(nv, 16);
-      t.nv[1] = max(nv - 16, 0);
+      const int pa = real ? __builtin_amdgcn_readlane(pg_phys, slot) : 0;
+      const int nv = real ? __builtin_amdgcn_readlane(pg_valid, slot) : 0;
+      t.nv[0] = nv;
+      t.nv[1] = nv;
       const size_t ta = (size_t)pa * sh.Hkv + j;
-      kA = (const bf16_t*)kv.k_pages + ta * (GP * D);
-      kB = kA + 16 * D;
-      vA = (const bf16_t*)kv.v_pages + ta * (GP * D);
-      vB = vA + 16;
+      const int row0 = real ? 8 * (l16 >> 2) + (l16 & 3) : 0;
+      k0 = (const bf16_t*)kv.k_pages + ta * (GP * D) + row0 * D;
+      k1 = k0 + (real ? 4 * D : 0);
+      vp = (const bf16_t*)kv.v_pages + ta * (GP * D) + (real ? l16 * GP : 0) + 8 * qd;
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      t.k[0][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(kA + l16 * D + ks * 32 + qd * 8));
-      t.k[1][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(kB + l16 * D + ks * 32 + qd * 8));
+      t.k[0][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(k0 + ks * 32 + qd * 8));
+      t.k[1][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(k1 + ks * 32 + qd * 8));
     }
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      t.v[nt][0] = *reinterpret_cast<const uint2*>(vA + (nt * 16 + l16) * GP + qd * 4);
-      t.v[nt][1] = *reinterpret_cast<const uint2*>(vB + (nt * 16 + l16) * GP + qd * 4);
-    }
+    for (int nt = 0; nt < NT; ++nt) t.v[nt] = *reinterpret_cast<const uint4*>(vp + nt * 16 * GP);
   };
 
+  // Exponentials are taken against a reference point m_run that is allowed to lag the true
+  // row maximum by up to kLag (log2 units): the accumulators are rescaled only when a row's
+  // maximum overtakes its reference by more than that, which after the first tile is rare.
+  // exp2(kLag) = 256 is far inside float / bfloat16 range, and (m_run, l, O) stay consistent.
+  constexpr float kLag = 8.0f;
+
   auto compute_tile = [&](Tile& t) {
-    const bool full = (t.nv[0] == 16) && (t.nv[1] == 16);
+    // valid tokens among this lane's 8 (tile tokens 8*qd .. 8*qd+7)
+    int lane_valid;
+    bool full;
+    if (GP == 16) {
+      full = (t.nv[0] == 16) && (t.nv[1] == 16);
+      lane_valid = (qd < 2 ? t.nv[0] : t.nv[1]) - 8 * (qd & 1);
+    } else {
+      full = t.nv[0] == 32;
+      lane_valid = t.nv[0] - 8 * qd;
+    }
     if (!full) {
       // slots past the end of the sequence may hold anything: clear them in V (0 * NaN = NaN)
+      const int cnt = max(0, min(8, lane_valid));
+      const uint32_t m0 = cnt >= 2 ? ~0u : (cnt == 1 ? 0xFFFFu : 0u);
+      const uint32_t m1 = cnt >= 4 ? ~0u : (cnt == 3 ? 0xFFFFu : 0u);
+      const uint32_t m2 = cnt >= 6 ? ~0u : (cnt == 5 ? 0xFFFFu : 0u);
+      const uint32_t m3 = cnt >= 8 ? ~0u : (cnt == 7 ? 0xFFFFu : 0u);
 #pragma unroll
-      for (int hf = 0; hf < 2; ++hf) {
-        const int cnt = max(0, min(4, t.nv[hf] - qd * 4));
-        const unsigned long long keep = cnt >= 4 ? ~0ull : ((1ull << (16 * cnt)) - 1ull);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          t.v[nt][hf].x &= (unsigned)keep;
-          t.v[nt][hf].y &= (unsigned)(keep >> 32);
-        }
+      for (int nt = 0; nt < NT; ++nt) {
+        t.v[nt].x &= m0;
+        t.v[nt].y &= m1;
+        t.v[nt].z &= m2;
+        t.v[nt].w &= m3;
       }
     }
+    // ---- phase 1: all score products back to back
+    f32x4_t sc[R][2];
 #pragma unroll
     for (int mt = 0; mt < R; ++mt) {
-      f32x4_t sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
+      sc[mt][0] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+      sc[mt][1] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[0][ks], qf[mt][ks], sA, 0, 0, 0);
-        sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][ks], qf[mt][ks], sB, 0, 0, 0);
+        sc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[0][ks], qf[mt][ks], sc[mt][0], 0, 0, 0);
+        sc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][ks], qf[mt][ks], sc[mt][1], 0, 0, 0);
       }
-      float s[8];
+    }
+    // ---- phase 2: row maxima of all row tiles, one lazy-rescale decision for the wavefront
+    float s[R][8], m_cand[R];
+#pragma unroll
+    for (int mt = 0; mt < R; ++mt) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        s[e] = sA[e] * scale_log2e;
-        s[4 + e] = sB[e] * scale_log2e;
+        s[mt][e] = sc[mt][0][e];
+        s[mt][4 + e] = sc[mt][1][e];
       }
       if (!full) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (qd * 4 + (e & 3) >= t.nv[e >> 2]) s[e] = -INFINITY;
+          if (e >= lane_valid) s[mt][e] = -INFINITY;
       }
-      float tmax = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float m_new = fmaxf(m_run[mt], tmax);
-      const float alpha = fast_exp2(m_run[mt] - m_new);
-      m_run[mt] = m_new;
-      f32x8_t p;
+      const float tm = vmax3(vmax3(s[mt][0], s[mt][1], s[mt][2]), vmax3(s[mt][3], s[mt][4], s[mt][5]),
+                            vmax(s[mt][6], s[mt][7]));
+      m_cand[mt] = max_over_lane_groups(tm) * scale_log2e;
+    }
+    bool any_up = false;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) p[e] = fast_exp2(s[e] - m_new);
-      // P as a bfloat16 pair hi + lo (16 mantissa bits): one bfloat16 alone costs 2^-9 of the
-      // spread of V per row, which outlier value channels push past the 2e-2 bound.
-      const bf16x8_t p_hi = __builtin_convertvector(p, bf16x8_t);
-      const f32x8_t hi_f = __builtin_convertvector(p_hi, f32x8_t);
-      const bf16x8_t p_lo = __builtin_convertvector(p - hi_f, bf16x8_t);
-      const f32x8_t lo_f = __builtin_convertvector(p_lo, f32x8_t);
-      // the row sum uses the same rounded values the products see
-      float psum = 0.f;
+    for (int mt = 0; mt < R; ++mt) any_up |= m_cand[mt] > m_run[mt] + kLag;
+    if (__any(any_up)) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) psum += hi_f[e] + lo_f[e];
-      l_run[mt] = l_run[mt] * alpha + psum;
+      for (int mt = 0; mt < R; ++mt) {
+        const bool up = m_cand[mt] > m_run[mt] + kLag;
+        const float alpha = up ? fast_exp2(m_run[mt] - m_cand[mt]) : 1.0f;
+        m_run[mt] = up ? m_cand[mt] : m_run[mt];
+        l_run[mt] *= alpha;
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
-        o[mt][nt] *= alpha;
-        const bf16x8_t vv = __builtin_bit_cast(bf16x8_t, make_uint4(t.v[nt][0].x, t.v[nt][0].y, t.v[nt][1].x, t.v[nt][1].y));
-        o[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, p_hi, o[mt][nt], 0, 0, 0);
-        o[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv, p_lo, o[mt][nt], 0, 0, 0);
+        for (int nt = 0; nt < NT; ++nt) o[mt][nt] *= alpha;
       }
     }
+    // ---- phase 3: numerators as a bfloat16 pair, value products.
+    // P = hi + lo with hi = p truncated to its top 16 bits (exact, no conversion) and
+    // lo = p - hi rounded: 16 mantissa bits in all.  A single bfloat16 would cost 2^-9 of the
+    // spread of V per row, which outlier value channels push past the 2e-2 bound.
+    // The hi products of a row tile are issued right after its numerators, so the matrix core
+    // works while the vector ALU does the next row tile; all lo products come last, far from
+    // the hi product that feeds the same accumulator.
+    bf16x8_t p_lo[R];
+#pragma unroll
+    for (int mt = 0; mt < R; ++mt) {
+      const float neg_m = -m_run[mt];
+      float p[8], psum = 0.f;
+      f32x8_t lo;
+      uint32_t pb[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        p[e] = fast_exp2(fmaf(s[mt][e], scale_log2e, neg_m));
+        psum += p[e];
+        pb[e] = __float_as_uint(p[e]);
+        lo[e] = p[e] - __uint_as_float(pb[e] & 0xFFFF0000u);
+      }
+      l_run[mt] += psum;
+      uint4 hi_bits;
+      hi_bits.x = __builtin_amdgcn_perm(pb[1], pb[0], 0x07060302u);
+      hi_bits.y = __builtin_amdgcn_perm(pb[3], pb[2], 0x07060302u);
+      hi_bits.z = __builtin_amdgcn_perm(pb[5], pb[4], 0x07060302u);
+      hi_bits.w = __builtin_amdgcn_perm(pb[7], pb[6], 0x07060302u);
+      const bf16x8_t p_hi = __builtin_bit_cast(bf16x8_t, hi_bits);
+      p_lo[mt] = __builtin_convertvector(lo, bf16x8_t);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        o[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, t.v[nt]), p_hi, o[mt][nt], 0, 0, 0);
+    }
+#pragma unroll
+    for (int mt = 0; mt < R; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+        o[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, t.v[nt]), p_lo[mt], o[mt][nt], 0, 0, 0);
   };
 
-  // ---- main loop, one tile of lookahead in registers
-  constexpr int TPR = 64 / PPT;   // tiles per page-id refill
-  Tile t0, t1;
-  if (ntw > 0) {
-    fetch_pages(0);
-    load_tile(t0, 0);
-  }
-  for (int n = 0; n < ntw; n += 2) {
-    if (n + 1 < ntw) {
-      if (((n + 1) % TPR) == 0) fetch_pages(n + 1);
-      load_tile(t1, n + 1);
+  // ---- main loop: NBUF tile buffers in registers, NBUF-1 tiles of lookahead.  A memory round
+  // trip costs about as much as computing two tiles and a wavefront has one wavefront per
+  // SIMD to itself, so latency is hidden by depth, not by occupancy.  Every load is issued
+  // unconditionally (see load_tile) so that the number of loads in flight at each use is a
+  // compile-time constant: a load behind a branch would force a full drain at the join.
+  Tile tb[NBUF];
+  for (int nb = 0; nb < ntw; nb += TPR) {
+    if (nb > 0) fetch_entries(nb);
+    decode_entries(nb);
+    const int ne = min(ntw, nb + TPR);
+#pragma unroll
+    for (int k = 0; k < NBUF - 1; ++k) load_tile(tb[k], nb + k, ne);
+    for (int n = nb; n < ne; n += NBUF) {
+#pragma unroll
+      for (int k = 0; k < NBUF; ++k) {
+        load_tile(tb[(k + NBUF - 1) % NBUF], n + k + NBUF - 1, ne);
+        if (n + k < ne) compute_tile(tb[k]);
+      }
     }
-    compute_tile(t0);
-    if (n + 2 < ntw) {
-      if (((n + 2) % TPR) == 0) fetch_pages(n + 2);
-      load_tile(t0, n + 2);
-    }
-    if (n + 1 < ntw) compute_tile(t1);
   }
 
   // each lane summed its own tokens; rows are spread over the 4 lane groups
 #pragma unroll
-  for (int mt = 0; mt < R; ++mt) {
-    l_run[mt] += __shfl_xor(l_run[mt], 16, 64);
-    l_run[mt] += __shfl_xor(l_run[mt], 32, 64);
-  }
+  for (int mt = 0; mt < R; ++mt) l_run[mt] = sum_over_lane_groups(l_run[mt]);
 
+  const size_t item = ((size_t)head * nchunk + chunk);
   if (SPLIT_PAGES) {
-    // ---- deterministic tree over the 4 wavefronts through LDS: (1->0, 3->2), then 2->0
+    // ---- one-round combine of the 4 wavefronts: everyone publishes (ref, sum, O) in LDS, then
+    // wavefront w combines channel tiles {2w, 2w+1} (D=128) of all four in wavefront order and
+    // stores its slice of the partial.  One barrier; the order is fixed, so is the result.
     typedef MergeSlot<D, R> Slot;
-    auto put = [&](float* slot) {
-      float* so = slot;
-      float* sm = slot + R * 16 * Slot::kStride;
+    constexpr int NTW = NT / 4;   // channel tiles per wavefront
+    {
+      float* so = lds + wave * Slot::kFloats;
+      float* sm = so + R * 16 * Slot::kStride;
       float* sl = sm + R * 16;
 #pragma unroll
       for (int mt = 0; mt < R; ++mt) {
@@ -284,42 +381,49 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, con
         for (int nt = 0; nt < NT; ++nt)
           *reinterpret_cast<f32x4_t*>(so + r * Slot::kStride + nt * 16 + qd * 4) = o[mt][nt];
       }
-    };
-    auto take = [&](const float* slot) {
-      const float* so = slot;
-      const float* sm = slot + R * 16 * Slot::kStride;
-      const float* sl = sm + R * 16;
+    }
+    __syncthreads();
 #pragma unroll
-      for (int mt = 0; mt < R; ++mt) {
-        const int r = mt * 16 + l16;
-        const float m_o = sm[r], l_o = sl[r];
-        const float m_n = fmaxf(m_run[mt], m_o);
-        const float wa = fast_exp2(m_run[mt] - m_n), wb = fast_exp2(m_o - m_n);
-        m_run[mt] = m_n;
-        l_run[mt] = l_run[mt] * wa + l_o * wb;
+    for (int mt = 0; mt < R; ++mt) {
+      const int r = mt * 16 + l16;
+      float mw[4], lw[4];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          const f32x4_t other = *reinterpret_cast<const f32x4_t*>(so + r * Slot::kStride + nt * 16 + qd * 4);
-          o[mt][nt] = o[mt][nt] * wa + other * wb;
+      for (int w = 0; w < 4; ++w) {
+        const float* sm = lds + w * Slot::kFloats + R * 16 * Slot::kStride;
+        mw[w] = sm[r];
+        lw[w] = sm[R * 16 + r];
+      }
+      const float m_all = vmax(vmax(mw[0], mw[1]), vmax(mw[2], mw[3]));
+      float wgt[4], l_all = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        wgt[w] = fast_exp2(mw[w] - m_all);
+        l_all = fmaf(lw[w], wgt[w], l_all);
+      }
+      const int rg = mt * 16 + l16;
+      if (rg < M) {
+        const size_t prow = item * sh.rows_max + rg;
+        if (wave == 0 && qd == 0) {
+          part.m[prow] = m_all;
+          part.l[prow] = l_all;
+        }
+#pragma unroll
+        for (int k = 0; k < NTW; ++k) {
+          const int nt = wave * NTW + k;
+          f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(lds + w * Slot::kFloats + r * Slot::kStride + nt * 16 + qd * 4);
+            acc += v * wgt[w];
+          }
+          *reinterpret_cast<f32x4_t*>(part.o + prow * D + nt * 16 + qd * 4) = acc;
         }
       }
-    };
-    float* slot0 = lds;
-    float* slot1 = lds + Slot::kFloats;
-    if (wave == 1) put(slot0);
-    if (wave == 3) put(slot1);
-    __syncthreads();
-    if (wave == 0) take(slot0);
-    if (wave == 2) take(slot1);
-    __syncthreads();
-    if (wave == 2) put(slot0);
-    __syncthreads();
-    if (wave != 0) return;
-    take(slot0);
+    }
+    return;
   }
 
   // ---- partial of this (sequence, head, chunk): un-normalised O, running max (log2 units), sum
-  const size_t item = ((size_t)b * sh.Hkv + j) * nchunk + chunk;
 #pragma unroll
   for (int mt = 0; mt < R; ++mt) {
     const int rg = rb * (R * 16) + mt * 16 + l16;
@@ -336,48 +440,69 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, con
   }
 }
 
+__global__ __launch_bounds__(256) void attn_prepare_kernel(KvView kv, Shape sh, const bf16_t* __restrict__ q,
+                                                           const int32_t* __restrict__ active_idx,
+                                                           const int32_t* __restrict__ active_count,
+                                                           const int32_t* __restrict__ sel_pages,
+                                                           const int32_t* __restrict__ sel_count, int cap,
+                                                           AttnPrepared prep) {
+  const int j = blockIdx.x, b = blockIdx.y;
+  const int P = min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages);
+  const int32_t* list = sel_pages ? sel_pages + ((size_t)b * sh.Hkv + j) * cap : nullptr;
+  const int U = list ? min(sel_count[b * sh.Hkv + j], cap) : P;
+  const int n_act = active_idx ? active_count[b] : sh.B;
+  prepare_head(kv, sh, b, j, list, U, active_idx, n_act, q, prep);
+}
+
+hipError_t launch_attn_prepare(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
+                               const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
+                               const int32_t* sel_count, int cap, const AttnPrepared& prep) {
+  if (batch <= 0) return hipSuccess;
+  dim3 grid(sh.Hkv, batch);
+  attn_prepare_kernel<<<grid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, sel_pages, sel_count,
+                                            cap, prep);
+  return hipGetLastError();
+}
+
 template <int D, int GP, int R, bool SPLIT>
-static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
-                             const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
-                             const int32_t* sel_count, int cap, int nchunk, const Partials& part) {
+static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
+                             int nchunk, const Partials& part) {
   const int nrbg = SPLIT ? 1 : (sh.rows_max + R * 16 * 4 - 1) / (R * 16 * 4);
-  const size_t lds_bytes = SPLIT ? 2 * MergeSlot<D, R>::kFloats * sizeof(float) : 0;
-  auto kern = attn_mfma_kernel<D, GP, R, SPLIT>;
-  if (lds_bytes > 48 * 1024) {
+  const size_t lds_bytes = SPLIT ? 4 * MergeSlot<D, R>::kFloats * sizeof(float) : 0;
+  constexpr int NBUF = (D == 128 && R == 4) ? 3 : 4;   // tile buffers that fit beside Q and O
+  auto kern = attn_mfma_kernel<D, GP, R, SPLIT, NBUF>;
+  static bool attr_set = false;   // per instantiation
+  if (lds_bytes > 48 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)lds_bytes);
     if (e != hipSuccess) return e;
+    attr_set = true;
   }
   const float scale_log2e = sh.sm_scale * 1.4426950408889634f;
   dim3 grid(nchunk, sh.Hkv * nrbg, batch);
-  kern<<<grid, 256, lds_bytes, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, sel_pages, sel_count, cap,
-                                     nchunk, nrbg, part, scale_log2e);
+  kern<<<grid, 256, lds_bytes, st>>>(kv, sh, prep, nchunk, nrbg, part, scale_log2e);
   return hipGetLastError();
 }
 
 template <int D, int GP>
-static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
-                            const int32_t* ai, const int32_t* ac, const int32_t* sp, const int32_t* sc, int cap,
+static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                             int nchunk, int rows_upper, const Partials& part) {
-  if (rows_upper <= 16) return launch_one<D, GP, 1, true>(st, kv, sh, batch, q, ai, ac, sp, sc, cap, nchunk, part);
-  if (rows_upper <= 32) return launch_one<D, GP, 2, true>(st, kv, sh, batch, q, ai, ac, sp, sc, cap, nchunk, part);
-  if (rows_upper <= 48) return launch_one<D, GP, 3, true>(st, kv, sh, batch, q, ai, ac, sp, sc, cap, nchunk, part);
-  if (rows_upper <= 64) return launch_one<D, GP, 4, true>(st, kv, sh, batch, q, ai, ac, sp, sc, cap, nchunk, part);
-  return launch_one<D, GP, 4, false>(st, kv, sh, batch, q, ai, ac, sp, sc, cap, nchunk, part);
+  if (rows_upper <= 16) return launch_one<D, GP, 1, true>(st, kv, sh, batch, prep, nchunk, part);
+  if (rows_upper <= 32) return launch_one<D, GP, 2, true>(st, kv, sh, batch, prep, nchunk, part);
+  if (rows_upper <= 48) return launch_one<D, GP, 3, true>(st, kv, sh, batch, prep, nchunk, part);
+  if (rows_upper <= 64) return launch_one<D, GP, 4, true>(st, kv, sh, batch, prep, nchunk, part);
+  return launch_one<D, GP, 4, false>(st, kv, sh, batch, prep, nchunk, part);
 }
 
-hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
-                            const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
-                            const int32_t* sel_count, int cap, int nchunk, int rows_upper, const Partials& part) {
+hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
+                            int nchunk, int rows_upper, const Partials& part) {
   if (batch <= 0 || nchunk <= 0) return hipSuccess;
   if (sh.d == 128) {
-    if (sh.g == 16)
-      return launch_dg<128, 16>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count, cap, nchunk, rows_upper, part);
-    return launch_dg<128, 32>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count, cap, nchunk, rows_upper, part);
+    if (sh.g == 16) return launch_dg<128, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part);
+    return launch_dg<128, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part);
   }
-  if (sh.g == 16)
-    return launch_dg<64, 16>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count, cap, nchunk, rows_upper, part);
-  return launch_dg<64, 32>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count, cap, nchunk, rows_upper, part);
+  if (sh.g == 16) return launch_dg<64, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part);
+  return launch_dg<64, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part);
 }
 
 }  // namespace losa
