@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph replay")
     ap.add_argument("--cpu-steps", type=int, default=12, help="oracle steps timed for cpu_baseline")
+    ap.add_argument("--calibration-copy-mib", type=int, default=256,
+                    help="size of the plain copy launched once as the reference for hardware byte counters")
     return ap.parse_args()
 
 
@@ -76,6 +78,14 @@ def main():
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
+
+    # ---- one plain copy of known size: what FETCH_SIZE / WRITE_SIZE are scaled by under rocprofv3 --pmc
+    if args.calibration_copy_mib > 0:
+        src = torch.zeros(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        L.losa_calibration_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- once per block: page bounds, then the dense initialisation (step 0) of every layer
     torch.cuda.synchronize()
@@ -152,6 +162,15 @@ def main():
     meta_bytes = sum(w.pages_per_seq) * w.Hkv * 2 * w.d * e
     step_bytes = attn_bytes + meta_bytes + 2 * w.batch * w.B * w.H * e + rows * (w.d + 1) * 4
     density = pages_per_launch / (sum(w.pages_per_seq) * w.Hkv)
+    # HBM bytes per launch from hardware counters, if a counter run of this workload was summarised
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"traffic_{w.name}.txt")
+    if os.path.exists(tfile):
+        vals = dict(l.split(":", 1) for l in open(tfile) if ":" in l and not l.startswith("#"))
+        try:
+            traffic = int(float(vals["attn_fetch_bytes_per_launch"]) + float(vals["attn_write_bytes_per_launch"]))
+        except (KeyError, ValueError):
+            traffic = None
 
     out = {
         "metric": "sparse-attn us per denoise step per layer (32k prefix)" if args.config == 1
@@ -175,7 +194,7 @@ def main():
         "page_bounds_GBps": round((sum(w.seq_lens) * w.Hkv * w.d * e + meta_bytes) / (bounds_us * 1e-6) / 1e9, 1),
         "roofline": {"kernel": "attn_partials (split-K sparse paged attention)", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "bytes_per_launch": int(attn_bytes), "us_per_launch": round(attn_us, 3)},
     }
 

@@ -183,6 +183,10 @@ typedef enum {
 } losa_stage;
 losa_status losa_profile_enable(losa_ctx* ctx, int32_t enable);
 losa_status losa_profile_read(losa_ctx* ctx, double* stage_ms, int64_t* stage_launches);
+/* A plain device-to-device copy kernel of `bytes` bytes (a multiple of 16, both pointers
+ * 16-byte aligned), enqueued on `stream`: the known-size reference that hardware byte
+ * counters (FETCH_SIZE / WRITE_SIZE) are scaled by when the kernels above are profiled. */
+losa_status losa_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

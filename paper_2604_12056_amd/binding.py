@@ -18,7 +18,7 @@ LOSA_SEL_TOPK, LOSA_SEL_FRACTION, LOSA_SEL_THRESHOLD = 0, 1, 2
 
 EXPORTS = ["losa_workspace_bytes", "losa_create", "losa_destroy", "losa_last_error", "losa_select_active",
            "losa_page_bounds", "losa_score_pages", "losa_sparse_attn", "losa_step", "losa_profile_enable",
-           "losa_profile_read"]
+           "losa_profile_read", "losa_calibration_copy"]
 STAGES = ["locality", "score", "topk", "attn", "merge", "bounds"]
 
 
@@ -76,6 +76,8 @@ def load_library() -> C.CDLL:
     lib.losa_profile_enable.argtypes = [vp, i32]
     lib.losa_profile_read.restype = C.c_int
     lib.losa_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.losa_calibration_copy.restype = C.c_int
+    lib.losa_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -208,3 +210,9 @@ def losa_profile_read(ctx: Context):
     cnt = (C.c_int64 * len(STAGES))()
     _check(ctx, load_library().losa_profile_read(ctx.handle, ms, cnt))
     return dict(zip(STAGES, list(ms))), dict(zip(STAGES, list(cnt)))
+
+
+def losa_calibration_copy(dst, src, stream=None):
+    """Plain copy of src into dst (same byte size): the known-size reference for byte counters."""
+    nbytes = src.numel() * src.element_size()
+    _check(None, load_library().losa_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))

@@ -12,6 +12,13 @@
 
 using namespace losa;
 
+namespace losa {
+__global__ __launch_bounds__(256) void calibration_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                               size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+}  // namespace losa
+
 struct losa_ctx {
   losa_config cfg;
   Shape sh;
@@ -353,6 +360,13 @@ losa_status losa_profile_enable(losa_ctx* ctx, int32_t enable) {
   ctx->profiling = enable != 0;
   ctx->rec_used = 0;
   return LOSA_OK;
+}
+
+losa_status losa_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || (bytes & 15) != 0 || (((uintptr_t)dst | (uintptr_t)src) & 15) != 0) return LOSA_ERR_INVALID_ARG;
+  if (bytes == 0) return LOSA_OK;
+  calibration_copy_kernel<<<2048, 256, 0, as_stream(stream)>>>((uint4*)dst, (const uint4*)src, bytes / 16);
+  return hipGetLastError() == hipSuccess ? LOSA_OK : LOSA_ERR_HIP;
 }
 
 losa_status losa_profile_read(losa_ctx* ctx, double* stage_ms, int64_t* stage_launches) {

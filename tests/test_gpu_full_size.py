@@ -1,0 +1,47 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration
+bench.py times (losa_step, top-n selection).  The numpy oracle is fast enough to check every
+output of these steps, so nothing is sampled: dense initialisation, then sparse steps, active
+masks / union sizes / (o_p, lse_p) against the oracle after each."""
+import numpy as np
+import pytest
+
+from oracle import losa_oracle as orc
+from paper_2604_12056_amd import synth
+
+from parity_util import Rig, check_page_bounds, run_steps_end_to_end
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(w, steps):
+    rig = Rig(w)
+    try:
+        check_page_bounds(rig)
+        run_steps_end_to_end(rig, steps, orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+        assert rig.near_ties <= 4, f"{rig.near_ties} near-tie decisions differed"
+    finally:
+        rig.close()
+
+
+def test_c1_full_32k():
+    _run(synth.config(1).replace(T=4), range(4))
+
+
+def test_c3_full_128k():
+    _run(synth.config(3).replace(T=3), range(3))
+
+
+def test_c2_ragged_batch_full():
+    w = synth.config(2)
+    _run(w.replace(T=3), range(3))
+
+
+@pytest.mark.parametrize("fraction,budget", [(0.05, 1024), (0.25, 2048), (1.0, 1024)])
+def test_c4_sweep_points(fraction, budget):
+    # batch 2 of the 4 sequences keeps the oracle's host memory and time modest; shapes are C4's
+    w = synth.config(4, active_fraction=fraction, budget_tokens=budget)
+    _run(w.replace(batch=2, seq_lens=w.seq_lens[:2], T=3), range(3))
+
+
+def test_c1_full_float_mode():
+    _run(synth.config(1, dtype="f32").replace(T=2, seq_lens=(8192 + 40,)), range(2))
