@@ -137,14 +137,18 @@ struct StageTimer {
   losa_ctx* ctx;
   hipStream_t st;
   size_t pair = (size_t)-1;
-  StageTimer(losa_ctx* c, hipStream_t s, int stage) : ctx(c), st(s) {
+  bool bound = false;   // the pair was handed to a launch that binds it to its dispatch
+  StageTimer(losa_ctx* c, hipStream_t s, int stage, bool bind_to_dispatch = false)
+      : ctx(c), st(s), bound(bind_to_dispatch) {
     if (!ctx->profiling || ctx->rec_used >= kMaxProfilePairs) return;
     pair = ctx->rec_used++;
     ctx->rec_stage[pair] = stage;
-    (void)hipEventRecord(ctx->events[2 * pair], st);
+    if (!bound) (void)hipEventRecord(ctx->events[2 * pair], st);
   }
+  hipEvent_t start() const { return pair != (size_t)-1 ? ctx->events[2 * pair] : nullptr; }
+  hipEvent_t stop() const { return pair != (size_t)-1 ? ctx->events[2 * pair + 1] : nullptr; }
   ~StageTimer() {
-    if (pair != (size_t)-1) (void)hipEventRecord(ctx->events[2 * pair + 1], st);
+    if (pair != (size_t)-1 && !bound) (void)hipEventRecord(ctx->events[2 * pair + 1], st);
   }
 };
 
@@ -261,9 +265,10 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
     if (e != hipSuccess) return hip_fail(ctx, "attn_prepare launch", e);
   }
   {
-    StageTimer timer(ctx, st, LOSA_STAGE_ATTN);
+    StageTimer timer(ctx, st, LOSA_STAGE_ATTN, /*bind_to_dispatch=*/mfma);
     if (mfma)
-      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, rows_upper, ctx->part);
+      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, rows_upper, ctx->part, timer.start(),
+                           timer.stop());
     else
       e = launch_attn_generic(st, ctx->cfg.dtype, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages,
                               sel_count, cap, nchunk, ctx->part);

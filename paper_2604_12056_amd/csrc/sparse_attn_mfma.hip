@@ -26,6 +26,7 @@
 //       64-row blocks and all walk the same tiles (served by the CU's L1 after the first).
 // Tiles of a (sequence, head) list are dealt round-robin to its workgroups, so every
 // workgroup gets the same number of tiles (within one) whatever the union size turns out to be.
+#include <hip/hip_ext.h>
 #include <math.h>
 
 #include "attn_prepare.h"
@@ -466,7 +467,7 @@ hipError_t launch_attn_prepare(hipStream_t st, const KvView& kv, const Shape& sh
 
 template <int D, int GP, int R, bool SPLIT>
 static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
-                             int nchunk, const Partials& part) {
+                             int nchunk, const Partials& part, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int nrbg = SPLIT ? 1 : (sh.rows_max + R * 16 * 4 - 1) / (R * 16 * 4);
   const size_t lds_bytes = SPLIT ? 4 * MergeSlot<D, R>::kFloats * sizeof(float) : 0;
   constexpr int NBUF = (D == 128 && R == 4) ? 3 : 4;   // tile buffers that fit beside Q and O
@@ -480,29 +481,33 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
   }
   const float scale_log2e = sh.sm_scale * 1.4426950408889634f;
   dim3 grid(nchunk, sh.Hkv * nrbg, batch);
-  kern<<<grid, 256, lds_bytes, st>>>(kv, sh, prep, nchunk, nrbg, part, scale_log2e);
+  if (ev_start && ev_stop)   // events bound to this dispatch: they read the kernel's own begin and end
+    hipExtLaunchKernelGGL(kern, grid, dim3(256), (uint32_t)lds_bytes, st, ev_start, ev_stop, 0, kv, sh, prep, nchunk,
+                          nrbg, part, scale_log2e);
+  else
+    kern<<<grid, 256, lds_bytes, st>>>(kv, sh, prep, nchunk, nrbg, part, scale_log2e);
   return hipGetLastError();
 }
 
 template <int D, int GP>
 static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
-                            int nchunk, int rows_upper, const Partials& part) {
-  if (rows_upper <= 16) return launch_one<D, GP, 1, true>(st, kv, sh, batch, prep, nchunk, part);
-  if (rows_upper <= 32) return launch_one<D, GP, 2, true>(st, kv, sh, batch, prep, nchunk, part);
-  if (rows_upper <= 48) return launch_one<D, GP, 3, true>(st, kv, sh, batch, prep, nchunk, part);
-  if (rows_upper <= 64) return launch_one<D, GP, 4, true>(st, kv, sh, batch, prep, nchunk, part);
-  return launch_one<D, GP, 4, false>(st, kv, sh, batch, prep, nchunk, part);
+                            int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1) {
+  if (rows_upper <= 16) return launch_one<D, GP, 1, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
+  if (rows_upper <= 32) return launch_one<D, GP, 2, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
+  if (rows_upper <= 48) return launch_one<D, GP, 3, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
+  if (rows_upper <= 64) return launch_one<D, GP, 4, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
+  return launch_one<D, GP, 4, false>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
 }
 
 hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
-                            int nchunk, int rows_upper, const Partials& part) {
+                            int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1) {
   if (batch <= 0 || nchunk <= 0) return hipSuccess;
   if (sh.d == 128) {
-    if (sh.g == 16) return launch_dg<128, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part);
-    return launch_dg<128, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part);
+    if (sh.g == 16) return launch_dg<128, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1);
+    return launch_dg<128, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1);
   }
-  if (sh.g == 16) return launch_dg<64, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part);
-  return launch_dg<64, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part);
+  if (sh.g == 16) return launch_dg<64, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1);
+  return launch_dg<64, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1);
 }
 
 }  // namespace losa
