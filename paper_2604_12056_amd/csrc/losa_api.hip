@@ -3,6 +3,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -13,6 +14,15 @@
 using namespace losa;
 
 namespace losa {
+__global__ void zero_ints_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+hipError_t launch_zero_ints(hipStream_t st, int32_t* p, int n) {
+  if (n <= 0) return hipSuccess;
+  zero_ints_kernel<<<(n + 255) / 256, 256, 0, st>>>(p, n);
+  return hipGetLastError();
+}
 __global__ __launch_bounds__(256) void calibration_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
                                                                size_t n16) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
@@ -30,10 +40,13 @@ struct losa_ctx {
   float* scores;
   uint32_t* rowmaps;
   int32_t* tickets;
+  int32_t* seq_tickets;   // [max_batch], kept at zero between launches
+  bool seq_tickets_clean = false;
   int32_t* sel_pages;
   int32_t* sel_count;
   Partials part;
   long part_items;
+  long target_workgroups;   // attention workgroups aimed at per launch
   AttnPrepared prep;
   char err[256];
   // measurement hooks
@@ -95,7 +108,7 @@ struct Carve {
 
 struct Layout {
   size_t delta, mask, active_idx, active_count, scores, rowmaps, tickets, sel_pages, sel_count, po, pm, pl;
-  size_t entries, q_act, ucount, mrows, total;
+  size_t entries, q_act, ucount, mrows, seq_tickets, total;
   long part_items;
 };
 
@@ -124,6 +137,7 @@ Layout make_layout(const losa_config* c) {
   L.q_act = cv.take(heads * rows_max * c->head_dim * 2);
   L.ucount = cv.take(heads * 4);
   L.mrows = cv.take(heads * 4);
+  L.seq_tickets = cv.take((size_t)c->max_batch * 4);
   L.total = cv.off;
   return L;
 }
@@ -188,7 +202,7 @@ losa_status hip_fail(losa_ctx* ctx, const char* what, hipError_t e) {
 int pick_nchunk(const losa_ctx* ctx, int batch, int upper, int row_groups) {
   const long heads = (long)batch * ctx->sh.Hkv;
   const long tiles = (upper + (32 / ctx->sh.g) - 1) / (32 / ctx->sh.g);
-  long want = kTargetWorkgroups / (heads * row_groups);
+  long want = ctx->target_workgroups / (heads * row_groups);
   const long fit = ctx->part_items / heads;
   if (want > fit) want = fit;
   if (want > tiles) want = tiles;
@@ -223,7 +237,19 @@ losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const v
     return fail(ctx, LOSA_ERR_INVALID_ARG, "unknown select mode %d", mode);
   }
   StageTimer timer(ctx, st, LOSA_STAGE_LOCALITY);
-  hipError_t e = launch_locality_delta(st, ctx->cfg.dtype, h_cur, h_prev, batch * B, ctx->sh.H, delta);
+  hipError_t e;
+  if (B <= 1024) {
+    if (!ctx->seq_tickets_clean) {   // first use: the ticket counters must start at zero; the kernel leaves them so
+      e = launch_zero_ints(st, ctx->seq_tickets, ctx->cfg.max_batch);
+      if (e != hipSuccess) return hip_fail(ctx, "ticket clear launch", e);
+      ctx->seq_tickets_clean = true;
+    }
+    e = launch_locality_select(st, ctx->cfg.dtype, h_cur, h_prev, batch, B, ctx->sh.H, mode, n, tau, delta, mask,
+                               active_idx, active_count, ctx->seq_tickets);
+    if (e != hipSuccess) return hip_fail(ctx, "locality_select launch", e);
+    return LOSA_OK;
+  }
+  e = launch_locality_delta(st, ctx->cfg.dtype, h_cur, h_prev, batch * B, ctx->sh.H, delta);
   if (e != hipSuccess) return hip_fail(ctx, "locality_delta launch", e);
   e = launch_rank_select(st, delta, batch, B, mode, n, tau, mask, active_idx, active_count);
   if (e != hipSuccess) return hip_fail(ctx, "rank_select launch", e);
@@ -329,10 +355,16 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   ctx->part.m = (float*)(base + L.pm);
   ctx->part.l = (float*)(base + L.pl);
   ctx->part_items = L.part_items;
+  ctx->target_workgroups = kTargetWorkgroups;
+  if (const char* env = getenv("LOSA_ATTN_WORKGROUPS")) {   // tuning knob: one workgroup per CU by default
+    const long v = atol(env);
+    if (v >= 1 && v <= L.part_items) ctx->target_workgroups = v;
+  }
   ctx->prep.entries = (int32_t*)(base + L.entries);
   ctx->prep.q_act = (uint16_t*)(base + L.q_act);
   ctx->prep.ucount = (int32_t*)(base + L.ucount);
   ctx->prep.mrows = (int32_t*)(base + L.mrows);
+  ctx->seq_tickets = (int32_t*)(base + L.seq_tickets);
   ctx->err[0] = 0;
   *out = ctx;
   return LOSA_OK;

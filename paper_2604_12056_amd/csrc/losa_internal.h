@@ -50,6 +50,11 @@ hipError_t launch_locality_delta(hipStream_t st, int dtype, const void* h_cur, c
 hipError_t launch_rank_select(hipStream_t st, const float* delta, int batch, int B, int mode, int n, float tau,
                               uint8_t* mask, int32_t* active_idx, int32_t* active_count);
 
+// fused: score per token + ranking by the last workgroup of each sequence (tickets: [batch] ints, zero on entry)
+hipError_t launch_locality_select(hipStream_t st, int dtype, const void* h_cur, const void* h_prev, int batch, int B,
+                                  int H, int mode, int n, float tau, float* delta, uint8_t* mask, int32_t* active_idx,
+                                  int32_t* active_count, int32_t* tickets);
+
 // ---- page_bounds.hip
 hipError_t launch_page_bounds(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
                               int first_page, int num_pages_in_range);

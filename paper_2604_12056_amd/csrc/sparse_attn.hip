@@ -209,8 +209,26 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, co
   constexpr int C4 = D / 4, CL = 256 / C4;
   __shared__ Acc red[CL][D];
   __shared__ Acc lred[CL];
-  __shared__ float wmax[4];
+  __shared__ float wmax[CL];
   const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  // The first KSPEC chunks of this thread are fetched before it is known how many chunks are
+  // live (slots exist for all nchunk work items): together with the counts below this makes
+  // the kernel one memory round trip deep instead of three.
+  constexpr int KSPEC = 8;
+  float pm_s[KSPEC], pl_s[KSPEC];
+  float4 po_s[KSPEC];
+  {
+    const int cl = tid / C4, c4 = tid % C4;
+    const size_t item0 = ((size_t)b * sh.Hkv + j) * nchunk;
+#pragma unroll
+    for (int k = 0; k < KSPEC; ++k) {
+      const int c = min(cl + CL * k, nchunk - 1);
+      const size_t prow = (item0 + c) * sh.rows_max + r;
+      pm_s[k] = part.m[prow];
+      pl_s[k] = part.l[prow];
+      po_s[k] = reinterpret_cast<const float4*>(part.o + prow * D)[c4];
+    }
+  }
   int M, U;
   if (ucount) {   // prepared by the matrix-core path
     M = min(mrows[b * sh.Hkv + j], sh.rows_max);
@@ -229,21 +247,40 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, co
   const int live = min(nchunk, ntiles);   // work item c exists iff tile c does
   const size_t item0 = ((size_t)b * sh.Hkv + j) * nchunk;
 
+  // thread (cl, c4) owns chunks cl, cl+CL, ... and channel quad c4
+  const int cl = tid / C4, c4 = tid % C4;
+  float mk[KSPEC];
+#pragma unroll
+  for (int k = 0; k < KSPEC; ++k) mk[k] = cl + CL * k < live ? pm_s[k] : -INFINITY;
   float mx = -INFINITY;
-  for (int c = tid; c < live; c += 256) mx = fmaxf(mx, part.m[(item0 + c) * sh.rows_max + r]);
-  mx = wave_max(mx);
-  if ((tid & 63) == 0) wmax[tid >> 6] = mx;
+#pragma unroll
+  for (int k = 0; k < KSPEC; ++k) mx = fmaxf(mx, mk[k]);
+  for (int c = cl + CL * KSPEC; c < live; c += CL) mx = fmaxf(mx, part.m[(item0 + c) * sh.rows_max + r]);
+  if (c4 == 0) wmax[cl] = mx;
   __syncthreads();
-  const float m_tot = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+  float m_tot = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < CL; ++k) m_tot = fmaxf(m_tot, wmax[k]);
   const size_t orow = ((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + hg;
   if (!(m_tot > -1.0e29f)) {   // no valid token at all: the neutral element of the merge
     if (tid < C4) reinterpret_cast<float4*>(o_p + orow * D)[tid] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (tid == 0) lse_p[orow] = -INFINITY;
     return;
   }
-  const int cl = tid / C4, c4 = tid % C4;
   Acc ax = 0, ay = 0, az = 0, aw = 0, lacc = 0;
-  for (int c = cl; c < live; c += CL) {
+#pragma unroll
+  for (int k = 0; k < KSPEC; ++k) {
+    if (cl + CL * k < live) {   // slots past `live` hold leftovers of earlier launches: never touch their values
+      const float dm = mk[k] - m_tot;
+      const Acc w = LOG2 ? (Acc)exp2f(dm) : (Acc)exp((double)dm);
+      ax += w * (Acc)po_s[k].x;
+      ay += w * (Acc)po_s[k].y;
+      az += w * (Acc)po_s[k].z;
+      aw += w * (Acc)po_s[k].w;
+      lacc += w * (Acc)pl_s[k];
+    }
+  }
+  for (int c = cl + CL * KSPEC; c < live; c += CL) {
     const size_t prow = (item0 + c) * sh.rows_max + r;
     const float dm = part.m[prow] - m_tot;
     const Acc w = LOG2 ? (Acc)exp2f(dm) : (Acc)exp((double)dm);

@@ -74,9 +74,10 @@ __device__ __forceinline__ float sum_over_lane_groups(float v) {
 }
 
 template <int D, int R>
-struct MergeSlot {   // LDS image of one wavefront's state
-  static constexpr int kStride = D + 4;   // +4 floats: 16-byte row writes of 16 lanes land on distinct banks
-  static constexpr int kFloats = R * 16 * (kStride + 2);
+struct MergeSlot {   // LDS image of one wavefront's state: O as [row tile][channel tile][lane] 16-byte
+                     // vectors (every access is lane-linear, so bank-conflict free), then ref[], sum[]
+  static constexpr int kOFloats = R * (D / 16) * 64 * 4;
+  static constexpr int kFloats = kOFloats + 2 * R * 16;
 };
 
 // Inputs of the matrix-core kernel are *prepared* per (sequence, KV head) by whoever decided
@@ -369,7 +370,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
     constexpr int NTW = NT / 4;   // channel tiles per wavefront
     {
       float* so = lds + wave * Slot::kFloats;
-      float* sm = so + R * 16 * Slot::kStride;
+      float* sm = so + Slot::kOFloats;
       float* sl = sm + R * 16;
 #pragma unroll
       for (int mt = 0; mt < R; ++mt) {
@@ -380,26 +381,35 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
-          *reinterpret_cast<f32x4_t*>(so + r * Slot::kStride + nt * 16 + qd * 4) = o[mt][nt];
+          *reinterpret_cast<f32x4_t*>(so + ((mt * NT + nt) * 64 + lane) * 4) = o[mt][nt];
       }
     }
     __syncthreads();
+    // all LDS reads of the combine are issued before the first is used
+    float mw[R][4], lw[R][4];
+    f32x4_t ov[R][NTW][4];
 #pragma unroll
     for (int mt = 0; mt < R; ++mt) {
       const int r = mt * 16 + l16;
-      float mw[4], lw[4];
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const float* sm = lds + w * Slot::kFloats + R * 16 * Slot::kStride;
-        mw[w] = sm[r];
-        lw[w] = sm[R * 16 + r];
+        const float* sm = lds + w * Slot::kFloats + Slot::kOFloats;
+        mw[mt][w] = sm[r];
+        lw[mt][w] = sm[R * 16 + r];
+#pragma unroll
+        for (int k = 0; k < NTW; ++k)
+          ov[mt][k][w] = *reinterpret_cast<const f32x4_t*>(lds + w * Slot::kFloats +
+                                                           ((mt * NT + wave * NTW + k) * 64 + lane) * 4);
       }
-      const float m_all = vmax(vmax(mw[0], mw[1]), vmax(mw[2], mw[3]));
+    }
+#pragma unroll
+    for (int mt = 0; mt < R; ++mt) {
+      const float m_all = vmax(vmax(mw[mt][0], mw[mt][1]), vmax(mw[mt][2], mw[mt][3]));
       float wgt[4], l_all = 0.f;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        wgt[w] = fast_exp2(mw[w] - m_all);
-        l_all = fmaf(lw[w], wgt[w], l_all);
+        wgt[w] = fast_exp2(mw[mt][w] - m_all);
+        l_all = fmaf(lw[mt][w], wgt[w], l_all);
       }
       const int rg = mt * 16 + l16;
       if (rg < M) {
@@ -410,14 +420,10 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
         }
 #pragma unroll
         for (int k = 0; k < NTW; ++k) {
-          const int nt = wave * NTW + k;
           f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(lds + w * Slot::kFloats + r * Slot::kStride + nt * 16 + qd * 4);
-            acc += v * wgt[w];
-          }
-          *reinterpret_cast<f32x4_t*>(part.o + prow * D + nt * 16 + qd * 4) = acc;
+          for (int w = 0; w < 4; ++w) acc += ov[mt][k][w] * wgt[w];
+          *reinterpret_cast<f32x4_t*>(part.o + prow * D + (wave * NTW + k) * 16 + qd * 4) = acc;
         }
       }
     }
