@@ -164,6 +164,20 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
                       losa_select_mode mode, float param, int32_t topk_pages,
                       void* o_p, float* lse_p, uint8_t* mask, int32_t* sel_count);
 
+/* (iv)+(v) Dense in-block attention and the final merge (Computation of the Suffix Tokens and
+ * Final Output; eq. full_attn): for every token i of the block and query head h,
+ *   s_b = sm_scale * q_{i,h} . k_b[t] over the B tokens t of the block (bidirectional),
+ *   L_b = ln sum_t exp(s_b),  o_b = sum_t exp(s_b - L_b) v_b[t],
+ *   out[i,h,:] = (e^{L_p} o_p + e^{L_b} o_b) / (e^{L_p} + e^{L_b})     with (o_p, L_p) as left by losa_step.
+ *   q          : T [batch*B, Hq, d]
+ *   k_b, v_b   : T [batch*B, Hkv, d]  keys / values of the block's own tokens (token-major, not paged)
+ *   o_p, lse_p : float, inputs
+ *   out        : float [batch*B, Hq, d]
+ *   o_b, lse_b : nullable float [batch*B, Hq, d] / [batch*B, Hq]: the block statistics on their own */
+losa_status losa_block_merge(losa_ctx* ctx, void* stream, int32_t batch, const void* q, const void* k_b,
+                             const void* v_b, const float* o_p, const float* lse_p, float* out, float* o_b,
+                             float* lse_b);
+
 /* Measurement hooks (the paper's latency breakdown names four components: criticality
  * estimation, locality pruning, cache management, attention computation; cache management
  * costs nothing here because reuse is "do not write").  While enabled, every launch made
@@ -179,7 +193,8 @@ typedef enum {
   LOSA_STAGE_ATTN = 3,     /* split-K attention kernel                 ("attention computation") */
   LOSA_STAGE_MERGE = 4,    /* split-K merge kernel                     ("attention computation") */
   LOSA_STAGE_BOUNDS = 5,   /* page min/max kernel (once per block) */
-  LOSA_NUM_STAGES = 6
+  LOSA_STAGE_BLOCK = 6,    /* in-block attention + final merge kernel */
+  LOSA_NUM_STAGES = 7
 } losa_stage;
 losa_status losa_profile_enable(losa_ctx* ctx, int32_t enable);
 losa_status losa_profile_read(losa_ctx* ctx, double* stage_ms, int64_t* stage_launches);

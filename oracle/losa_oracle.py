@@ -240,6 +240,30 @@ def losa_step(cache: PrefixCache, step_index: int,
     return tr
 
 
+def block_attention_and_merge(q: np.ndarray, k_b: np.ndarray, v_b: np.ndarray, o_p: np.ndarray, L_p: np.ndarray,
+                              B: int, scale: Optional[float] = None
+                              ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Dense attention inside the block and the final merge with the prefix statistics
+    (Methodology, Computation of the Suffix Tokens and Final Output).
+    q [batch*B, Hq, d], k_b / v_b [batch*B, Hkv, d] (storage types), o_p [batch*B, Hq, d],
+    L_p [batch*B, Hq] (float64).  Returns (O, o_b, L_b)."""
+    qf, kf, vf = widen(q), widen(k_b), widen(v_b)
+    rows, Hq, d = qf.shape
+    Hkv = kf.shape[1]
+    G = Hq // Hkv
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    O = np.empty_like(qf)
+    o_b = np.empty_like(qf)
+    L_b = np.empty((rows, Hq))
+    for b in range(rows // B):
+        sl = slice(b * B, (b + 1) * B)
+        for h in range(Hq):
+            ob, Lb = prefix_attention(qf[sl, h], kf[sl, h // G], vf[sl, h // G], scale)
+            o_b[sl, h], L_b[sl, h] = ob, Lb
+            O[sl, h], _ = merge_partials(np.asarray(o_p[sl, h], dtype=np.float64), np.asarray(L_p[sl, h], dtype=np.float64), ob, Lb)
+    return O, o_b, L_b
+
+
 def dense_block_attention(Q_b: np.ndarray, K_all: np.ndarray, V_all: np.ndarray) -> np.ndarray:
     """Full attention of one head, O = softmax(Q_b [K_p,K_b]^T / sqrt(d)) [V_p,V_b]
     (Preliminaries, eq. full_attn), as a direct row-by-row softmax."""

@@ -18,8 +18,8 @@ LOSA_SEL_TOPK, LOSA_SEL_FRACTION, LOSA_SEL_THRESHOLD = 0, 1, 2
 
 EXPORTS = ["losa_workspace_bytes", "losa_create", "losa_destroy", "losa_last_error", "losa_select_active",
            "losa_page_bounds", "losa_score_pages", "losa_sparse_attn", "losa_step", "losa_profile_enable",
-           "losa_profile_read", "losa_calibration_copy"]
-STAGES = ["locality", "score", "topk", "attn", "merge", "bounds"]
+           "losa_profile_read", "losa_calibration_copy", "losa_block_merge"]
+STAGES = ["locality", "score", "topk", "attn", "merge", "bounds", "block"]
 
 
 class LosaError(RuntimeError):
@@ -76,6 +76,8 @@ def load_library() -> C.CDLL:
     lib.losa_profile_enable.argtypes = [vp, i32]
     lib.losa_profile_read.restype = C.c_int
     lib.losa_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.losa_block_merge.restype = C.c_int
+    lib.losa_block_merge.argtypes = [vp, vp, i32, p, p, p, p, p, p, p, p]
     lib.losa_calibration_copy.restype = C.c_int
     lib.losa_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
     _lib = lib
@@ -216,3 +218,10 @@ def losa_calibration_copy(dst, src, stream=None):
     """Plain copy of src into dst (same byte size): the known-size reference for byte counters."""
     nbytes = src.numel() * src.element_size()
     _check(None, load_library().losa_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+def losa_block_merge(ctx: Context, q, k_b, v_b, o_p, lse_p, out, o_b=None, lse_b=None, batch: Optional[int] = None,
+                     stream=None):
+    batch = int(lse_p.shape[0] // ctx.cfg.block_size) if batch is None else batch
+    _check(ctx, load_library().losa_block_merge(ctx.handle, _stream(stream), batch, _ptr(q), _ptr(k_b), _ptr(v_b),
+                                               _ptr(o_p), _ptr(lse_p), _ptr(out), _ptr(o_b), _ptr(lse_b)))

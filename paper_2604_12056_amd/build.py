@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "liblosa.so")
 
-SOURCES = ["losa_api.hip", "select_active.hip", "page_bounds.hip", "score_pages.hip", "sparse_attn.hip", "sparse_attn_mfma.hip"]
+SOURCES = ["losa_api.hip", "select_active.hip", "page_bounds.hip", "score_pages.hip", "sparse_attn.hip", "sparse_attn_mfma.hip", "block_merge.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -492,6 +492,20 @@ losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, con
                           sel_count, cap, /*rows_upper=*/0, /*prepared=*/false, (float*)o_p, lse_p);
 }
 
+losa_status losa_block_merge(losa_ctx* ctx, void* stream, int32_t batch, const void* q, const void* k_b,
+                             const void* v_b, const float* o_p, const float* lse_p, float* out, float* o_b,
+                             float* lse_b) {
+  if (!ctx) return LOSA_ERR_INVALID_ARG;
+  if (batch < 1 || batch > ctx->cfg.max_batch)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "batch %d outside 1..max_batch (%d)", batch, ctx->cfg.max_batch);
+  if (!q || !k_b || !v_b || !o_p || !lse_p || !out) return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_block_merge: NULL pointer");
+  hipStream_t st = as_stream(stream);
+  StageTimer timer(ctx, st, LOSA_STAGE_BLOCK);
+  hipError_t e = launch_block_merge(st, ctx->cfg.dtype, ctx->sh, batch, q, k_b, v_b, o_p, lse_p, out, o_b, lse_b);
+  if (e != hipSuccess) return hip_fail(ctx, "block_merge launch", e);
+  return LOSA_OK;
+}
+
 losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t step_index, const void* h_cur,
                       const void* h_prev, const void* q, losa_select_mode mode, float param, int32_t topk_pages,
                       void* o_p, float* lse_p, uint8_t* mask, int32_t* sel_count) {

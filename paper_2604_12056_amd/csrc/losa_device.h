@@ -41,6 +41,11 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+__device__ __forceinline__ float exp_acc(float x) { return expf(x); }
+__device__ __forceinline__ double exp_acc(double x) { return exp(x); }
+__device__ __forceinline__ float log_acc(float x) { return logf(x); }
+__device__ __forceinline__ double log_acc(double x) { return log(x); }
+
 // Exclusive prefix sum of one int per thread over a block of up to 1024 threads.
 // `wave_tot` is LDS scratch of 17 ints.  Returns the exclusive prefix; *total gets the block sum.
 // Every thread of the block must call it.

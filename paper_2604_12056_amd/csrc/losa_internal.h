@@ -88,4 +88,9 @@ hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, 
                              const int32_t* sel_count, int cap, int nchunk, const AttnPrepared* prep,
                              const Partials& part, float* o_p, float* lse_p);
 
+// ---- block_merge.hip
+hipError_t launch_block_merge(hipStream_t st, int dtype, const Shape& sh, int batch, const void* q, const void* k_b,
+                              const void* v_b, const float* o_p, const float* lse_p, float* out, float* o_b,
+                              float* lse_b);
+
 }  // namespace losa

@@ -27,8 +27,6 @@ constexpr int kTileTok = 32;   // tokens per LDS tile
 // within reach of float summation error once outlier channels push |q.k| into the hundreds.
 template <typename T> struct AccOf { typedef float type; };
 template <> struct AccOf<float> { typedef double type; };
-__device__ __forceinline__ float exp_acc(float x) { return expf(x); }
-__device__ __forceinline__ double exp_acc(double x) { return exp(x); }
 
 template <typename T, int D, int GP>
 __global__ __launch_bounds__(256) void attn_partials_generic_kernel(

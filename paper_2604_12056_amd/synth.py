@@ -211,6 +211,22 @@ def make_block_states(w: Workload) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     return h, q, picked
 
 
+def make_block_kv(w: Workload) -> Tuple[np.ndarray, np.ndarray]:
+    """Keys / values of the block's own tokens per step, [T, batch*B, Hkv, d]: N(0,1) times the
+    same per-channel scales as the prefix keys / values, redrawn every step (the block's K_b,
+    V_b change at each denoising step)."""
+    rows = w.batch * w.B
+    sK = channel_scales(w, 0, w.Hkv)
+    sV = channel_scales(w, 1, w.Hkv)
+    r = _rng(w.seed, 50)
+    kb = np.empty((w.T, rows, w.Hkv, w.d), dtype=np.uint16 if w.dtype == "bf16" else np.float32)
+    vb = np.empty_like(kb)
+    for t in range(w.T):
+        kb[t] = store(r.standard_normal((rows, w.Hkv, w.d), dtype=np.float32) * sK[None], w.dtype)
+        vb[t] = store(r.standard_normal((rows, w.Hkv, w.d), dtype=np.float32) * sV[None], w.dtype)
+    return kb, vb
+
+
 def make_page_table(w: Workload) -> Tuple[np.ndarray, np.ndarray, int]:
     """Logical -> physical page map: one seeded permutation over all pages of the batch,
     so a sequence's pages are scattered through the pool."""

@@ -107,6 +107,31 @@ def test_run_twice_is_bitwise_identical(rig):
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
 
 
+def test_block_merge_gives_the_full_attention_output(rig):
+    """In-block attention + final merge on top of the prefix statistics, against the oracle."""
+    w, blk = rig.w, rig.blk
+    check_page_bounds(rig)
+    run_steps_end_to_end(rig, range(2), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+    kb, vb = synth.make_block_kv(w)
+    from paper_2604_12056_amd.device_inputs import to_device
+    dkb, dvb = to_device(kb[1], blk.q.device), to_device(vb[1], blk.q.device)
+    out = torch.empty_like(blk.o_p); o_b = torch.empty_like(blk.o_p); lse_b = torch.empty_like(blk.lse_p)
+    L.losa_block_merge(rig.ctx, blk.q[1], dkb, dvb, blk.o_p, blk.lse_p, out, o_b, lse_b)
+    torch.cuda.synchronize()
+    # the oracle merges the GPU's own prefix statistics (already compared above), so only this stage is judged
+    O_ref, ob_ref, Lb_ref = orc.block_attention_and_merge(rig.inp.q[1], kb[1], vb[1], blk.o_p.cpu().numpy(),
+                                                          blk.lse_p.cpu().numpy(), w.B)
+    t = 2e-2 if w.dtype == "bf16" else 1e-4
+    assert np.abs(out.cpu().numpy() - O_ref).max() <= t
+    assert np.abs(o_b.cpu().numpy() - ob_ref).max() <= t
+    assert np.abs(lse_b.cpu().numpy() - Lb_ref).max() <= t
+    # an empty prefix (lse_p = -inf) must give the block attention alone, whatever o_p holds
+    blk.lse_p.fill_(float("-inf")); blk.o_p.fill_(float("nan"))
+    L.losa_block_merge(rig.ctx, blk.q[1], dkb, dvb, blk.o_p, blk.lse_p, out)
+    torch.cuda.synchronize()
+    assert np.abs(out.cpu().numpy() - ob_ref).max() <= t
+
+
 # ------------------------------------------------------------------ degenerate shapes
 @pytest.mark.parametrize("seq_lens", [(1,), (15,), (16,), (17, 1, 33)])
 def test_tiny_prefixes(seq_lens):

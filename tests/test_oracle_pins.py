@@ -347,6 +347,31 @@ def test_union_never_grows_when_fewer_tokens_are_active():
     assert np.all(np.diff(sizes, axis=0) >= 0)          # |U(A)| <= |U(A')| for A subset A' (top-n sets are nested)
 
 
+def test_dense_prefix_plus_block_merge_equals_full_attention_over_prefix_and_block():
+    # eq. full_attn through scipy, for every token and head, GQA included
+    inp = _small_inputs(seq_lens=(100, 37))
+    w = inp.w
+    kb, vb = synth.make_block_kv(w)
+    cache = orc.PrefixCache(inp.K, inp.V, w.g)
+    o = np.zeros((w.batch * w.B, w.Hq, w.d)); L = np.zeros((w.batch * w.B, w.Hq))
+    orc.losa_step(cache, 0, None, None, inp.q[0], 0, 0, 0, w.B, w.Hq, o, L)
+    O, o_b, L_b = orc.block_attention_and_merge(inp.q[0], kb[0], vb[0], o, L, w.B)
+    qf = synth.load(inp.q[0]).astype(np.float64)
+    kbf, vbf = synth.load(kb[0]).astype(np.float64), synth.load(vb[0]).astype(np.float64)
+    for b in range(w.batch):
+        Kp, Vp = synth.load(inp.K[b]).astype(np.float64), synth.load(inp.V[b]).astype(np.float64)
+        sl = slice(b * w.B, (b + 1) * w.B)
+        for h in range(w.Hq):
+            j = h // w.G
+            K_all = np.concatenate([Kp[:, j], kbf[sl, j]]); V_all = np.concatenate([Vp[:, j], vbf[sl, j]])
+            full = softmax(qf[sl, h] @ K_all.T / np.sqrt(w.d), axis=-1) @ V_all
+            np.testing.assert_allclose(O[sl, h], full, atol=1e-12)
+            np.testing.assert_allclose(L_b[sl, h], logsumexp(qf[sl, h] @ kbf[sl, j].T / np.sqrt(w.d), axis=-1), atol=1e-12)
+    # an empty prefix (L_p = -inf) leaves the block attention alone
+    O2, o_b2, _ = orc.block_attention_and_merge(inp.q[0], kb[0], vb[0], np.zeros_like(o), np.full_like(L, -np.inf), w.B)
+    np.testing.assert_allclose(O2, o_b2, atol=1e-14)
+
+
 def test_empty_active_set_is_a_no_op():
     inp = _small_inputs()
     w = inp.w
