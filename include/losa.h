@@ -54,9 +54,17 @@ typedef enum { LOSA_BF16 = 0, LOSA_F32 = 1 } losa_dtype;
 
 /* How the active set is chosen from the locality scores (Methodology, Locality Pruning):
  * TOPK: the `param` tokens with the largest score (the paper's rule; it uses 5 of 16);
- * FRACTION: top n with n = max(1, floor(param*B + 0.5));  THRESHOLD: score > param.
+ * FRACTION: top n with n = max(1, floor(param*B + 0.5));  THRESHOLD: score > param;
+ * MASS: tokens in descending score order until their running sum reaches param (in [0,1])
+ * times the block's total score (the 50 % line of the paper's locality heat maps is
+ * param = 0.5); nothing is selected when the total is zero or param is zero.
  * Ties: larger score first, then smaller token index. */
-typedef enum { LOSA_SEL_TOPK = 0, LOSA_SEL_FRACTION = 1, LOSA_SEL_THRESHOLD = 2 } losa_select_mode;
+typedef enum {
+  LOSA_SEL_TOPK = 0,
+  LOSA_SEL_FRACTION = 1,
+  LOSA_SEL_THRESHOLD = 2,
+  LOSA_SEL_MASS = 3
+} losa_select_mode;
 
 typedef struct {
   int32_t max_batch;         /* sequences per call, >= 1 */

@@ -33,7 +33,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
 
-SEL_TOPK, SEL_FRACTION, SEL_THRESHOLD = 0, 1, 2
+SEL_TOPK, SEL_FRACTION, SEL_THRESHOLD, SEL_MASS = 0, 1, 2, 3
 
 
 def widen(x: np.ndarray) -> np.ndarray:
@@ -63,14 +63,30 @@ def num_active(mode: int, param: float, B: int) -> int:
 
 
 def active_set(delta: np.ndarray, mode: int, param: float) -> np.ndarray:
-    """A: the tokens ranked highest by Delta (top-n), or those with Delta > tau.
-    Returned ascending by token index."""
+    """A: the tokens ranked highest by Delta (top-n), those with Delta > tau, or the shortest
+    run of top tokens carrying a fraction tau of the total.  Returned ascending by token index."""
     d32 = np.asarray(delta, dtype=np.float64).astype(np.float32)
     B = d32.shape[0]
     if mode == SEL_THRESHOLD:
         return np.nonzero(d32 > np.float32(param))[0].astype(np.int32)
-    n = num_active(mode, param, B)
     order = sorted(range(B), key=lambda i: (-float(d32[i]), i))
+    if mode == SEL_MASS:
+        # Locality figures (threshold line): tokens in descending score order until their
+        # running sum reaches the fraction `param` of the block total; float32 sums in that order.
+        total = np.float32(0.0)
+        for i in order:
+            total = np.float32(total + d32[i])
+        n = 0
+        if total > 0 and np.float32(param) > 0:
+            target = np.float32(np.float32(param) * total)
+            run, n = np.float32(0.0), B
+            for k, i in enumerate(order):
+                run = np.float32(run + d32[i])
+                if run >= target:
+                    n = k + 1
+                    break
+        return np.array(sorted(order[:n]), dtype=np.int32)
+    n = num_active(mode, param, B)
     return np.array(sorted(order[:n]), dtype=np.int32)
 
 

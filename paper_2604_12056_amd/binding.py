@@ -14,7 +14,7 @@ from .build import LIB_PATH
 
 LOSA_OK, LOSA_ERR_INVALID_ARG, LOSA_ERR_UNSUPPORTED, LOSA_ERR_WORKSPACE, LOSA_ERR_HIP = range(5)
 LOSA_BF16, LOSA_F32 = 0, 1
-LOSA_SEL_TOPK, LOSA_SEL_FRACTION, LOSA_SEL_THRESHOLD = 0, 1, 2
+LOSA_SEL_TOPK, LOSA_SEL_FRACTION, LOSA_SEL_THRESHOLD, LOSA_SEL_MASS = 0, 1, 2, 3
 
 EXPORTS = ["losa_workspace_bytes", "losa_create", "losa_destroy", "losa_last_error", "losa_select_active",
            "losa_page_bounds", "losa_score_pages", "losa_sparse_attn", "losa_step", "losa_profile_enable",

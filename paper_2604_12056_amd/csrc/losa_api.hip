@@ -233,26 +233,22 @@ losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const v
   } else if (mode == LOSA_SEL_THRESHOLD) {
     if (isnan(param)) return fail(ctx, LOSA_ERR_INVALID_ARG, "threshold is NaN");
     tau = param;
+  } else if (mode == LOSA_SEL_MASS) {
+    if (!(param >= 0.f && param <= 1.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "mass fraction must be in [0,1]");
+    tau = param;
   } else {
     return fail(ctx, LOSA_ERR_INVALID_ARG, "unknown select mode %d", mode);
   }
   StageTimer timer(ctx, st, LOSA_STAGE_LOCALITY);
   hipError_t e;
-  if (B <= 1024) {
-    if (!ctx->seq_tickets_clean) {   // first use: the ticket counters must start at zero; the kernel leaves them so
-      e = launch_zero_ints(st, ctx->seq_tickets, ctx->cfg.max_batch);
-      if (e != hipSuccess) return hip_fail(ctx, "ticket clear launch", e);
-      ctx->seq_tickets_clean = true;
-    }
-    e = launch_locality_select(st, ctx->cfg.dtype, h_cur, h_prev, batch, B, ctx->sh.H, mode, n, tau, delta, mask,
-                               active_idx, active_count, ctx->seq_tickets);
-    if (e != hipSuccess) return hip_fail(ctx, "locality_select launch", e);
-    return LOSA_OK;
+  if (!ctx->seq_tickets_clean) {   // first use: the ticket counters must start at zero; the kernel leaves them so
+    e = launch_zero_ints(st, ctx->seq_tickets, ctx->cfg.max_batch);
+    if (e != hipSuccess) return hip_fail(ctx, "ticket clear launch", e);
+    ctx->seq_tickets_clean = true;
   }
-  e = launch_locality_delta(st, ctx->cfg.dtype, h_cur, h_prev, batch * B, ctx->sh.H, delta);
-  if (e != hipSuccess) return hip_fail(ctx, "locality_delta launch", e);
-  e = launch_rank_select(st, delta, batch, B, mode, n, tau, mask, active_idx, active_count);
-  if (e != hipSuccess) return hip_fail(ctx, "rank_select launch", e);
+  e = launch_locality_select(st, ctx->cfg.dtype, h_cur, h_prev, batch, B, ctx->sh.H, mode, n, tau, delta, mask,
+                             active_idx, active_count, ctx->seq_tickets);
+  if (e != hipSuccess) return hip_fail(ctx, "locality_select launch", e);
   return LOSA_OK;
 }
 
@@ -536,7 +532,8 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
                        ctx->sel_pages, sc, cap, fuse_prepare);
   if (s != LOSA_OK) return s;
   // the host knows |A| in the top-n modes, so the attention can be shaped for n*G rows
-  const int rows_upper = mode == LOSA_SEL_THRESHOLD ? 0 : select_count(ctx, (int)mode, param) * ctx->sh.G;
+  const bool counted = mode == LOSA_SEL_TOPK || mode == LOSA_SEL_FRACTION;
+  const int rows_upper = counted ? select_count(ctx, (int)mode, param) * ctx->sh.G : 0;
   return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, ctx->sel_pages, sc,
                           cap, rows_upper, fuse_prepare, (float*)o_p, lse_p);
 }

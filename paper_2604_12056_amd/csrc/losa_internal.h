@@ -45,11 +45,6 @@ struct AttnPrepared {
 };
 
 // ---- select_active.hip
-hipError_t launch_locality_delta(hipStream_t st, int dtype, const void* h_cur, const void* h_prev,
-                                 int rows, int H, float* delta);
-hipError_t launch_rank_select(hipStream_t st, const float* delta, int batch, int B, int mode, int n, float tau,
-                              uint8_t* mask, int32_t* active_idx, int32_t* active_count);
-
 // fused: score per token + ranking by the last workgroup of each sequence (tickets: [batch] ints, zero on entry)
 hipError_t launch_locality_select(hipStream_t st, int dtype, const void* h_cur, const void* h_prev, int batch, int B,
                                   int H, int mode, int n, float tau, float* delta, uint8_t* mask, int32_t* active_idx,

@@ -90,6 +90,15 @@ def check_select_active(rig: Rig, t: int, mode: int, param: float):
             for i in set(A) ^ set(A_ref):
                 assert abs(ref[b * w.B + i] - param) <= NEAR_TIE * max(1.0, abs(param))
                 rig.near_ties += 1
+        elif mode == orc.SEL_MASS:
+            # a different count is acceptable only if the running sum sits within the near-tie band of the target
+            if len(A) != len(A_ref):
+                srt = np.sort(ref[b * w.B:(b + 1) * w.B])[::-1]
+                k = min(len(A), len(A_ref))
+                assert abs(srt[:k].sum() - param * srt.sum()) <= NEAR_TIE * max(1.0, srt.sum())
+                rig.near_ties += 1
+            else:
+                assert set(A.tolist()) == set(A_ref.tolist())
         else:
             rig.near_ties += check_near_tie_sets(set(A.tolist()), set(A_ref.tolist()), ref[b * w.B:(b + 1) * w.B],
                                                  len(A_ref), f"active set seq {b}")

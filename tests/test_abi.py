@@ -71,6 +71,9 @@ def test_workspace_checks_and_argument_validation(lib):
         assert lib.losa_select_active(ctx, None, 1, None, fake, 0, 5.0, fake, fake, fake, fake) == inv   # NULL input
         assert lib.losa_select_active(ctx, None, 1, fake, fake, 7, 5.0, fake, fake, fake, fake) == inv   # bad mode
         assert lib.losa_select_active(ctx, None, 1, fake, fake, 1, 1.5, fake, fake, fake, fake) == inv   # fraction > 1
+        assert lib.losa_select_active(ctx, None, 1, fake, fake, 3, 1.5, fake, fake, fake, fake) == inv   # mass > 1
+        assert lib.losa_block_merge(ctx, None, 1, fake, None, fake, fake, fake, fake, None, None) == inv  # NULL k_b
+        assert lib.losa_block_merge(ctx, None, 9, fake, fake, fake, fake, fake, fake, None, None) == inv  # batch > max
         assert lib.losa_page_bounds(ctx, None, None, 0, -1) == inv
         assert lib.losa_page_bounds(ctx, None, C.byref(kv), -1, -1) == inv
         bad = binding.losa_kv(fake, fake, None, fake, fake, fake, 2, 100, 0)

@@ -48,6 +48,8 @@ def test_select_active_all_modes(rig):
     check_select_active(rig, 1, orc.SEL_THRESHOLD, 0.01)
     check_select_active(rig, 1, orc.SEL_THRESHOLD, 1e9)        # empty active set
     check_select_active(rig, 1, orc.SEL_TOPK, 0.0)
+    for tau in (0.3, 0.5, 0.9, 0.0):
+        check_select_active(rig, 1, orc.SEL_MASS, tau)
     assert rig.near_ties == 0
 
 
@@ -77,6 +79,15 @@ def test_losa_step_end_to_end(rig):
     w = rig.w
     check_page_bounds(rig)
     run_steps_end_to_end(rig, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+    assert rig.near_ties <= 2
+
+
+def test_losa_step_threshold_and_mass_modes(rig):
+    """The selection modes whose count is only known on the device (full-row attention shape)."""
+    w = rig.w
+    check_page_bounds(rig)
+    run_steps_end_to_end(rig, range(2), orc.SEL_THRESHOLD, 0.01, w.topk_pages)
+    run_steps_end_to_end(rig, [2 % w.T or 1], orc.SEL_MASS, 0.5, w.topk_pages)
     assert rig.near_ties <= 2
 
 

@@ -159,6 +159,29 @@ def test_active_set_rules(golden_dir):
     assert [synth.active_count(f, 64) for f in (0.05, 0.10, 0.25, 0.50, 1.0)] == [3, 6, 16, 32, 64]
 
 
+def test_active_set_cumulative_mass_rule():
+    # hand values: sorted 8, 4, 2, 1, 1 (total 16); half the mass is reached by the first token alone,
+    # 0.75 needs two (12 >= 12), 0.76 needs three, all of it needs all five
+    delta = np.array([1.0, 8.0, 2.0, 4.0, 1.0])
+    np.testing.assert_array_equal(orc.active_set(delta, orc.SEL_MASS, 0.5), [1])
+    np.testing.assert_array_equal(orc.active_set(delta, orc.SEL_MASS, 0.75), [1, 3])
+    np.testing.assert_array_equal(orc.active_set(delta, orc.SEL_MASS, 0.76), [1, 2, 3])
+    np.testing.assert_array_equal(orc.active_set(delta, orc.SEL_MASS, 1.0), [0, 1, 2, 3, 4])
+    np.testing.assert_array_equal(orc.active_set(delta, orc.SEL_MASS, 0.0), [])
+    np.testing.assert_array_equal(orc.active_set(np.zeros(4), orc.SEL_MASS, 0.5), [])
+    # brute force: the chosen set is a prefix of the descending order, reaches the mass, and is minimal
+    rng = np.random.default_rng(12)
+    for _ in range(50):
+        d = rng.random(int(rng.integers(1, 20))) ** 4
+        tau = float(rng.random())
+        A = orc.active_set(d, orc.SEL_MASS, tau)
+        srt = np.sort(d)[::-1]
+        assert sorted(d[A], reverse=True) == list(srt[:len(A)])
+        assert d[A].sum() >= tau * d.sum() * (1 - 1e-6)
+        if len(A) > 1:
+            assert srt[:len(A) - 1].sum() < tau * d.sum() * (1 + 1e-6)
+
+
 def test_active_set_brute_force():
     rng = np.random.default_rng(7)
     for _ in range(50):
