@@ -38,13 +38,84 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph replay")
     ap.add_argument("--cpu-steps", type=int, default=12, help="oracle steps timed for cpu_baseline")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: KV load and latency versus the number of active tokens "
+                         "and the page budget on configuration C4 (one JSON line per point)")
     ap.add_argument("--calibration-copy-mib", type=int, default=256,
                     help="size of the plain copy launched once as the reference for hardware byte counters")
     return ap.parse_args()
 
 
+def sweep(args):
+    """Synthetic analogue of the paper's KV-load-versus-active-tokens figure: configuration C4
+    (Llama-3-8B-like, batch 4, 64k prefix, pages of 32, block 64), active fraction in
+    {5,10,25,50,100} % x budget in {1024,2048,4096} tokens, plus the dense all-active all-pages
+    step.  100 % active is the per-query sparse baseline the paper calls QUEST (Adapted)."""
+    import numpy as np
+    import torch
+
+    from paper_2604_12056_amd import binding as L
+    from paper_2604_12056_amd import synth
+    from paper_2604_12056_amd.device_inputs import DeviceBlock, DeviceLayer, config_of
+
+    dev = "cuda:0"
+    base = synth.config(4)
+    K, V = synth.make_kv(base)
+    indptr, indices, total = synth.make_page_table(base)
+    lens = np.array(base.seq_lens, dtype=np.int32)
+    layer = None
+    ctx = L.losa_create(config_of(base, max_topk_pages=4096 // base.g), dev)
+    e = 2
+    for frac in (0.05, 0.10, 0.25, 0.50, 1.00):
+        for budget in (1024, 2048, 4096):
+            w = synth.config(4, active_fraction=frac, budget_tokens=budget)
+            h, q, picked = synth.make_block_states(w)
+            inp = synth.Inputs(w, K, V, h, q, picked, lens, indptr, indices, total)
+            if layer is None:
+                layer = DeviceLayer(inp, dev)
+                L.losa_page_bounds(ctx, layer.kv)
+            blk = DeviceBlock(inp, dev)
+            mode, param = L.LOSA_SEL_TOPK, float(w.n_active)
+
+            def step(t, diag=None):
+                L.losa_step(ctx, layer.kv, t, blk.h[t] if t else None, blk.h[t - 1] if t else None, blk.q[t], mode,
+                            param, w.topk_pages, blk.o_p, blk.lse_p, None, diag)
+
+            step(0)
+            for t in range(1, w.T):
+                step(t)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step(0)
+            e1.record()
+            torch.cuda.synchronize()
+            dense_us = e0.elapsed_time(e1) * 1e3
+            cnt = torch.zeros((w.T, w.batch, w.Hkv), dtype=torch.int32, device=dev)
+            reps = 4
+            e0.record()
+            for _ in range(reps):
+                for t in range(1, w.T):
+                    step(t, cnt[t])
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (reps * (w.T - 1))
+            pages = cnt[1:].sum(dim=(1, 2)).float().mean().item()
+            density = pages / (sum(w.pages_per_seq) * w.Hkv)
+            print(json.dumps({"workload": w.name, "active_tokens": w.n_active, "active_fraction": frac,
+                              "budget_tokens": budget, "kv_density": round(density, 4),
+                              "kv_bytes_per_step": int(pages * w.g * w.d * 2 * e), "sparse_step_us": round(us, 2),
+                              "dense_step_us": round(dense_us, 2), "speedup_vs_dense": round(dense_us / us, 2)}),
+                  flush=True)
+    ctx.close()
+
+
 def main():
     args = parse_args()
+    if args.sweep:
+        if args.gpus != 1:
+            sys.exit(2)
+        return sweep(args)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only; run with --gpus 1 (no multi-GPU path exists)",
               file=sys.stderr)
