@@ -29,7 +29,6 @@
 #include <hip/hip_ext.h>
 #include <math.h>
 
-#include "attn_prepare.h"
 #include "losa_device.h"
 #include "losa_internal.h"
 
@@ -334,6 +333,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
         o[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, t.v[nt]), p_lo[mt], o[mt][nt], 0, 0, 0);
+    // Scheduling hint for this region: alternate one matrix instruction with a few vector
+    // instructions, so the numerators of the next row tile are computed while the matrix core
+    // works on the products of the previous one (one wavefront per SIMD: nobody else would).
+#pragma unroll
+    for (int i = 0; i < 2 * R * NT; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // 3 VALU
+    }
   };
 
   // ---- main loop: NBUF tile buffers in registers, NBUF-1 tiles of lookahead.  A memory round
@@ -447,6 +454,13 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
   }
 }
 
+// Builds the prepared inputs of attn_mfma_kernel when the selection kernel has not done so
+// (stand-alone losa_sparse_attn, and the dense initialisation): resolves the page list
+// (logical ids, or every page when sel_pages is NULL) to entries and gathers the query rows
+// of the active tokens (every token when active_idx is NULL).  kPrepSlices workgroups per
+// (sequence, KV head) share the work, so no thread walks a long chain of dependent loads.
+constexpr int kPrepSlices = 16;
+
 __global__ __launch_bounds__(256) void attn_prepare_kernel(KvView kv, Shape sh, const bf16_t* __restrict__ q,
                                                            const int32_t* __restrict__ active_idx,
                                                            const int32_t* __restrict__ active_count,
@@ -454,18 +468,48 @@ __global__ __launch_bounds__(256) void attn_prepare_kernel(KvView kv, Shape sh, 
                                                            const int32_t* __restrict__ sel_count, int cap,
                                                            AttnPrepared prep) {
   const int j = blockIdx.x, b = blockIdx.y;
-  const int P = min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages);
-  const int32_t* list = sel_pages ? sel_pages + ((size_t)b * sh.Hkv + j) * cap : nullptr;
-  const int U = list ? min(sel_count[b * sh.Hkv + j], cap) : P;
+  const int gtid = blockIdx.z * 256 + threadIdx.x, gthreads = kPrepSlices * 256;
+  const int head = b * sh.Hkv + j;
+  const int base = kv.page_indptr[b];
+  const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
+  const int L = kv.seq_lens[b];
+  const int32_t* list = sel_pages ? sel_pages + (size_t)head * cap : nullptr;
+  const int U = max(0, min(list ? min(sel_count[head], cap) : P, sh.max_pages));
   const int n_act = active_idx ? active_count[b] : sh.B;
-  prepare_head(kv, sh, b, j, list, U, active_idx, n_act, q, prep);
+  int32_t* ent = prep.entries + (size_t)head * sh.max_pages;
+  for (int i = gtid; i < U; i += gthreads) {
+    const int logical = list ? list[i] : i;
+    int e = 0;
+    if ((unsigned)logical < (unsigned)P) {
+      const int ph = kv.page_indices[base + logical];
+      const int nv = max(0, min(sh.g, L - logical * sh.g));
+      if ((unsigned)ph < (unsigned)kv.num_pages && ph < (1 << kEntryShift)) e = ph | (nv << kEntryShift);
+    }
+    ent[i] = e;
+  }
+  const int M = max(0, min(n_act, sh.B)) * sh.G;
+  const int vpr = sh.d / 8;   // 16-byte vectors per query row
+  uint4* dst = reinterpret_cast<uint4*>(prep.q_act + (size_t)head * sh.rows_max * sh.d);
+  for (int v = gtid; v < M * vpr; v += gthreads) {
+    const int r = v / vpr, cv = v % vpr;
+    const int a = r / sh.G, hg = r % sh.G;
+    const int tok = active_idx ? active_idx[(size_t)b * sh.B + a] : a;
+    uint4 val = make_uint4(0u, 0u, 0u, 0u);
+    if ((unsigned)tok < (unsigned)sh.B)
+      val = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + hg) * sh.d)[cv];
+    dst[v] = val;
+  }
+  if (gtid == 0) {
+    prep.ucount[head] = U;
+    prep.mrows[head] = M;
+  }
 }
 
 hipError_t launch_attn_prepare(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
                                const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
                                const int32_t* sel_count, int cap, const AttnPrepared& prep) {
   if (batch <= 0) return hipSuccess;
-  dim3 grid(sh.Hkv, batch);
+  dim3 grid(sh.Hkv, batch, kPrepSlices);
   attn_prepare_kernel<<<grid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, sel_pages, sel_count,
                                             cap, prep);
   return hipGetLastError();
