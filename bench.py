@@ -155,8 +155,15 @@ def main():
         src = torch.zeros(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         L.losa_calibration_copy(dst, src)
+        e0, e1 = ev(), ev()
+        e0.record()
+        L.losa_calibration_copy(dst, src)
+        e1.record()
         torch.cuda.synchronize()
+        copy_gbps = 2.0 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9      # bytes read + bytes written
         del src, dst
+    else:
+        copy_gbps = None
 
     # ---- once per block: page bounds, then the dense initialisation (step 0) of every layer
     torch.cuda.synchronize()
@@ -211,6 +218,38 @@ def main():
         torch.cuda.synchronize()
         total_ms, launch = e0.elapsed_time(e1), "hipGraph replay"
     us_per_step = total_ms * 1e3 / args.steps
+    # spread over further replays of the same K steps (the reported value stays the first timed replay)
+    spread = None
+    if not args.no_graph:
+        reps = []
+        for _ in range(9):
+            e0, e1 = ev(), ev()
+            e0.record()
+            graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            reps.append(e0.elapsed_time(e1) * 1e3 / args.steps)
+        reps = np.sort(np.array(reps + [us_per_step]))
+        spread = {"median": round(float(np.median(reps)), 3), "p10": round(float(np.percentile(reps, 10)), 3),
+                  "p90": round(float(np.percentile(reps, 90)), 3), "replays": int(reps.size)}
+        # the same steps on ONE layer only: its KV stays in the last-level cache between steps (warm figure)
+        warm_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(warm_graph):
+            for i in range(args.steps):
+                t = 1 + i % (T - 1)
+                L.losa_step(ctx, layers[0].kv, t, h[t], h[t - 1], q[t], mode, param, topk,
+                            blocks[0].o_p, blocks[0].lse_p)
+        warm_graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        warm_graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        warm_us = e0.elapsed_time(e1) * 1e3 / args.steps
+        del warm_graph
+    else:
+        warm_us = None
 
     # ---- second pass over the same steps with per-kernel events on the launch stream
     L.losa_profile_enable(ctx, True)
@@ -254,6 +293,9 @@ def main():
                    "budget_pages_per_query": w.topk_pages, "layers_rotated": NL, "denoise_steps": T,
                    "step_kind": "sparse (step index >= 1), full losa_step", "launch": launch},
         "eager_us_per_step": round(eager_us, 3),
+        "us_per_step_spread": spread,
+        "warm_single_layer_us_per_step": round(warm_us, 3) if warm_us is not None else None,
+        "measured_copy_GBps": round(copy_gbps, 1) if copy_gbps is not None else None,
         "step_hbm_GBps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
         "step_bytes": int(step_bytes),
         "union_pages_per_kv_head": round(pages_per_launch / (w.batch * w.Hkv), 1),
@@ -266,6 +308,7 @@ def main():
         "roofline": {"kernel": "attn_partials (split-K sparse paged attention)", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "frac_of_measured_copy": round(achieved / copy_gbps, 4) if copy_gbps else None,
                      "bytes_per_launch": int(attn_bytes), "us_per_launch": round(attn_us, 3)},
     }
 

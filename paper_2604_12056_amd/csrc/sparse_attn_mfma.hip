@@ -29,6 +29,8 @@
 #include <hip/hip_ext.h>
 #include <math.h>
 
+#include <type_traits>
+
 #include "losa_device.h"
 #include "losa_internal.h"
 
@@ -95,7 +97,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
   constexpr int NT = D / 16;    // channel tiles of the output
   constexpr int PPT = 32 / GP;  // pages per 32-token tile
   constexpr int TPR = 64 / PPT; // tiles covered by one page-entry fetch (one entry per lane)
-  extern __shared__ float lds[];
+  extern __shared__ __attribute__((aligned(16))) float lds[];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l16 = lane & 15, qd = lane >> 4;
@@ -370,69 +372,91 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
 
   const size_t item = ((size_t)head * nchunk + chunk);
   if (SPLIT_PAGES) {
-    // ---- one-round combine of the 4 wavefronts: everyone publishes (ref, sum, O) in LDS, then
-    // wavefront w combines channel tiles {2w, 2w+1} (D=128) of all four in wavefront order and
-    // stores its slice of the partial.  One barrier; the order is fixed, so is the result.
+    // ---- one-round combine of the 4 wavefronts: wavefront w owns channel tiles {w*NTW ..} of
+    // the partial.  Everyone publishes (ref, sum) and the O tiles it does NOT own in LDS (its
+    // own stay in registers), then reads the three other wavefronts' versions of its tiles,
+    // combines the four in wavefront order and stores its slice.  One barrier; the order is
+    // fixed, so is the result.  The register file is indexed by the wavefront number, hence
+    // one specialisation per wavefront behind a uniform branch.
     typedef MergeSlot<D, R> Slot;
     constexpr int NTW = NT / 4;   // channel tiles per wavefront
-    {
-      float* so = lds + wave * Slot::kFloats;
-      float* sm = so + Slot::kOFloats;
-      float* sl = sm + R * 16;
+    auto publish = [&](auto wv) {
+      constexpr int W = decltype(wv)::value;
+      {
+        float* so = lds + W * Slot::kFloats;
+        float* sm = so + Slot::kOFloats;
+        float* sl = sm + R * 16;
+#pragma unroll
+        for (int mt = 0; mt < R; ++mt) {
+          const int r = mt * 16 + l16;
+          if (qd == 0) {
+            sm[r] = m_run[mt];
+            sl[r] = l_run[mt];
+          }
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt)
+            if (nt / NTW != W) *reinterpret_cast<f32x4_t*>(so + ((mt * NT + nt) * 64 + lane) * 4) = o[mt][nt];
+        }
+      }
+    };
+    auto combine = [&](auto wv) {
+      constexpr int W = decltype(wv)::value;
+      // all LDS reads of the combine are issued before the first is used
+      float mw[R][4], lw[R][4];
+      f32x4_t ov[R][NTW][4];
 #pragma unroll
       for (int mt = 0; mt < R; ++mt) {
         const int r = mt * 16 + l16;
-        if (qd == 0) {
-          sm[r] = m_run[mt];
-          sl[r] = l_run[mt];
-        }
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-          *reinterpret_cast<f32x4_t*>(so + ((mt * NT + nt) * 64 + lane) * 4) = o[mt][nt];
+        for (int w = 0; w < 4; ++w) {
+          const float* sm = lds + w * Slot::kFloats + Slot::kOFloats;
+          mw[mt][w] = sm[r];
+          lw[mt][w] = sm[R * 16 + r];
+#pragma unroll
+          for (int k = 0; k < NTW; ++k)
+            ov[mt][k][w] = w == W ? o[mt][W * NTW + k]
+                                  : *reinterpret_cast<const f32x4_t*>(lds + w * Slot::kFloats +
+                                                                      ((mt * NT + W * NTW + k) * 64 + lane) * 4);
+        }
       }
+#pragma unroll
+      for (int mt = 0; mt < R; ++mt) {
+        const float m_all = vmax(vmax(mw[mt][0], mw[mt][1]), vmax(mw[mt][2], mw[mt][3]));
+        float wgt[4], l_all = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          wgt[w] = fast_exp2(mw[mt][w] - m_all);
+          l_all = fmaf(lw[mt][w], wgt[w], l_all);
+        }
+        const int rg = mt * 16 + l16;
+        if (rg < M) {
+          const size_t prow = item * sh.rows_max + rg;
+          if (W == 0 && qd == 0) {
+            part.m[prow] = m_all;
+            part.l[prow] = l_all;
+          }
+#pragma unroll
+          for (int k = 0; k < NTW; ++k) {
+            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) acc += ov[mt][k][w] * wgt[w];
+            *reinterpret_cast<f32x4_t*>(part.o + prow * D + (W * NTW + k) * 16 + qd * 4) = acc;
+          }
+        }
+      }
+    };
+    switch (wave) {
+      case 0: publish(std::integral_constant<int, 0>{}); break;
+      case 1: publish(std::integral_constant<int, 1>{}); break;
+      case 2: publish(std::integral_constant<int, 2>{}); break;
+      default: publish(std::integral_constant<int, 3>{}); break;
     }
     __syncthreads();
-    // all LDS reads of the combine are issued before the first is used
-    float mw[R][4], lw[R][4];
-    f32x4_t ov[R][NTW][4];
-#pragma unroll
-    for (int mt = 0; mt < R; ++mt) {
-      const int r = mt * 16 + l16;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float* sm = lds + w * Slot::kFloats + Slot::kOFloats;
-        mw[mt][w] = sm[r];
-        lw[mt][w] = sm[R * 16 + r];
-#pragma unroll
-        for (int k = 0; k < NTW; ++k)
-          ov[mt][k][w] = *reinterpret_cast<const f32x4_t*>(lds + w * Slot::kFloats +
-                                                           ((mt * NT + wave * NTW + k) * 64 + lane) * 4);
-      }
-    }
-#pragma unroll
-    for (int mt = 0; mt < R; ++mt) {
-      const float m_all = vmax(vmax(mw[mt][0], mw[mt][1]), vmax(mw[mt][2], mw[mt][3]));
-      float wgt[4], l_all = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        wgt[w] = fast_exp2(mw[mt][w] - m_all);
-        l_all = fmaf(lw[mt][w], wgt[w], l_all);
-      }
-      const int rg = mt * 16 + l16;
-      if (rg < M) {
-        const size_t prow = item * sh.rows_max + rg;
-        if (wave == 0 && qd == 0) {
-          part.m[prow] = m_all;
-          part.l[prow] = l_all;
-        }
-#pragma unroll
-        for (int k = 0; k < NTW; ++k) {
-          f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int w = 0; w < 4; ++w) acc += ov[mt][k][w] * wgt[w];
-          *reinterpret_cast<f32x4_t*>(part.o + prow * D + (wave * NTW + k) * 16 + qd * 4) = acc;
-        }
-      }
+    switch (wave) {
+      case 0: combine(std::integral_constant<int, 0>{}); break;
+      case 1: combine(std::integral_constant<int, 1>{}); break;
+      case 2: combine(std::integral_constant<int, 2>{}); break;
+      default: combine(std::integral_constant<int, 3>{}); break;
     }
     return;
   }
