@@ -30,14 +30,55 @@ template <typename T> __device__ __forceinline__ float load_elem(const T* p);
 template <> __device__ __forceinline__ float load_elem<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
 template <> __device__ __forceinline__ float load_elem<float>(const float* p) { return *p; }
 
+// ---- cross-lane traffic without LDS round trips: DPP row operations inside each row of 16
+// lanes, then the two lane-swap instructions across rows.
+// DPP controls (CDNA ISA, "DPP_CTRL"): row_shr:n = 0x110+n, row_ror:n = 0x120+n,
+// row_bcast15 = 0x142 (lane 15 of each row to the next row), row_bcast31 = 0x143.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ int dpp_move(int v) {   // lanes without a source, or masked out, get 0
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, false);
+}
+
+// Combines the four rows once every lane of a row already holds that row's result.
+template <typename F>
+__device__ __forceinline__ uint32_t across_rows(uint32_t v, F op) {
+  const auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  const uint32_t h = op(a[0], a[1]);
+  const auto c = __builtin_amdgcn_permlane32_swap(h, h, false, false);
+  return op(c[0], c[1]);
+}
+template <typename F>
+__device__ __forceinline__ uint32_t wave_all_reduce(uint32_t v, F op) {
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x121, 0xF, 0xF, false));
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x122, 0xF, 0xF, false));
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x124, 0xF, 0xF, false));
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x128, 0xF, 0xF, false));
+  return across_rows(v, op);
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  return __uint_as_float(wave_all_reduce(__float_as_uint(v), [](uint32_t a, uint32_t b) {
+    return __float_as_uint(__uint_as_float(a) + __uint_as_float(b));
+  }));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return __uint_as_float(wave_all_reduce(__float_as_uint(v), [](uint32_t a, uint32_t b) {
+    return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b)));
+  }));
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+  return wave_all_reduce(v, [](uint32_t a, uint32_t b) { return a < b ? a : b; });
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  return wave_all_reduce(v, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
+}
+// Inclusive prefix sum over the 64 lanes.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v += dpp_move<0x111>(v);
+  v += dpp_move<0x112>(v);
+  v += dpp_move<0x114>(v);
+  v += dpp_move<0x118>(v);         // scanned inside each row of 16
+  v += dpp_move<0x142, 0xA>(v);    // rows 1 and 3 take the total of the row before them
+  v += dpp_move<0x143, 0xC>(v);    // rows 2 and 3 take the total of the first 32 lanes
   return v;
 }
 
@@ -51,22 +92,16 @@ __device__ __forceinline__ double log_acc(double x) { return log(x); }
 // Every thread of the block must call it.
 __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int* total) {
   const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
-  int incl = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int t = __shfl_up(incl, o, 64);
-    if (lane >= o) incl += t;
-  }
+  const int incl = wave_inclusive_scan(v);
   if (lane == 63) wave_tot[wid] = incl;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int w = 0; w < nw; ++w) { int t = wave_tot[w]; wave_tot[w] = run; run += t; }
-    wave_tot[16] = run;
+  int base = 0, sum = 0;
+  for (int w = 0; w < nw; ++w) {
+    const int t = wave_tot[w];
+    base += w < wid ? t : 0;
+    sum += t;
   }
-  __syncthreads();
-  const int base = wave_tot[wid];
-  *total = wave_tot[16];
+  *total = sum;
   __syncthreads();   // scratch may be reused by the next call
   return base + incl - v;
 }

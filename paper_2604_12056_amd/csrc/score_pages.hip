@@ -214,8 +214,10 @@ struct SelectOut {
 
 // Inclusive suffix scan over 256 histogram buckets by one wavefront: lane l owns buckets
 // 255-4l .. 252-4l (descending).  Returns through LDS the bucket where the running count from
-// the top first reaches `need`, and how many are still needed inside that bucket.
-__device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need, uint32_t* s_bucket, int* s_need) {
+// the top first reaches `need`, how many are still needed inside that bucket, and how many
+// keys the bucket holds.
+__device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need, uint32_t* s_bucket, int* s_need,
+                                                  int* s_count) {
   const int lane = threadIdx.x;   // caller guarantees threadIdx.x < 64
   int c[4], tot = 0;
 #pragma unroll
@@ -223,12 +225,7 @@ __device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need
     c[k] = (int)hist[255 - 4 * lane - k];
     tot += c[k];
   }
-  int incl = tot;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(incl, o, 64);
-    if (lane >= o) incl += t;
-  }
+  const int incl = wave_inclusive_scan(tot);
   int above = incl - tot;   // keys in buckets owned by lower lanes (= higher buckets)
   if (above < need && incl >= need) {
 #pragma unroll
@@ -236,6 +233,7 @@ __device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need
       if (above < need && above + c[k] >= need) {
         *s_bucket = (uint32_t)(255 - 4 * lane - k);
         *s_need = need - above;
+        *s_count = c[k];
       }
       above += c[k];
     }
@@ -246,71 +244,89 @@ __device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need
 // pages [t*E, t*E+E); P <= 256*E), fused with the union and the hand-over described above.
 // The radix starts at the highest bit in which the row's keys differ (a block min/max finds
 // it), so the first histogram is already spread over many buckets instead of piling every
-// key onto the few exponent patterns the scores share.
+// key onto the few exponent patterns the scores share.  As soon as the bucket that holds the
+// K-th key has at most kRankMax keys, those are copied to LDS and ranked against each other
+// directly (one thread per candidate), which replaces the remaining histogram passes.
+constexpr int kRankMax = 256;
 template <int E>
 __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
                                                            const float* __restrict__ scores, int topk, SelectOut out) {
   constexpr int WORDS = 256 * E / 32;
   __shared__ uint32_t hist[256];
   __shared__ uint32_t rowbits[WORDS];
-  __shared__ uint32_t s_bucket, s_lo[4], s_hi[4];
-  __shared__ int s_need, s_last;
+  __shared__ __attribute__((aligned(16))) uint32_t cand[kRankMax];
+  __shared__ uint32_t s_bucket, s_lo[4], s_hi[4], s_kth;
+  __shared__ int s_need, s_last, s_count, s_ncand;
   __shared__ int scan[17];
   const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
   const int head = b * sh.Hkv + j;
+  const int p_first = tid * E;
+  // The row's scores are fetched before anything else is known: the address depends on kernel
+  // arguments only and every row of the score buffer exists, so these loads travel together
+  // with the loads of the counts below (entries past the sequence's pages are masked later).
+  const float* row = scores + ((size_t)head * sh.rows_max + min(r, sh.rows_max - 1)) * sh.max_pages;
+  float raw[E];
+  if (p_first + E <= sh.max_pages && (sh.max_pages & 3) == 0) {
+#pragma unroll
+    for (int i = 0; i < E; i += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(row + p_first + i);
+      raw[i] = v.x;
+      raw[i + 1] = v.y;
+      raw[i + 2] = v.z;
+      raw[i + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < E; ++i) raw[i] = row[min(p_first + i, sh.max_pages - 1)];
+  }
   const int n_act = min(active_count[b], sh.B);
   const int M = n_act * sh.G;
+  const int base = kv.page_indptr[b];
+  const int P = max(0, min(kv.page_indptr[b + 1] - base, sh.max_pages));
+  const int L = kv.seq_lens[b];
+
+  if (r == sh.rows_max) {
+    // The extra workgroup of every (sequence, head) gathers the head's active query rows into
+    // the dense buffer the attention kernel reads, off the path of the selection.  Indices are
+    // clamped so that every load can be issued before the one it depends on has been checked.
+    if (out.prep.entries == nullptr || M <= 0) return;
+    constexpr int QV = 4;   // 16-byte vectors per thread per sweep
+    const int vpr = sh.d / 8;
+    const bf16_t* q = (const bf16_t*)out.q;
+    uint4* dst = reinterpret_cast<uint4*>(out.prep.q_act + (size_t)head * sh.rows_max * sh.d);
+    for (int v0 = tid; v0 < M * vpr; v0 += 256 * QV) {
+      int tok[QV];
+#pragma unroll
+      for (int k = 0; k < QV; ++k) tok[k] = out.active_idx[(size_t)b * sh.B + min((v0 + 256 * k) / vpr, M - 1) / sh.G];
+      uint4 qv[QV];
+#pragma unroll
+      for (int k = 0; k < QV; ++k) {
+        const int rr = min((v0 + 256 * k) / vpr, M - 1), cv = (v0 + 256 * k) % vpr;
+        const int tc = (unsigned)tok[k] < (unsigned)sh.B ? tok[k] : 0;
+        qv[k] = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tc) * sh.Hq + j * sh.G + rr % sh.G) * sh.d)[cv];
+      }
+#pragma unroll
+      for (int k = 0; k < QV; ++k)
+        if (v0 + 256 * k < M * vpr)
+          dst[v0 + 256 * k] = (unsigned)tok[k] < (unsigned)sh.B ? qv[k] : make_uint4(0u, 0u, 0u, 0u);
+    }
+    return;
+  }
   if (r >= M) return;
-  const int P = max(0, min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages));
   const int words = (sh.max_pages + 31) / 32;
   const int a = r / sh.G, h = j * sh.G + r % sh.G;
   int32_t* tk = out.topk_out ? out.topk_out + (((size_t)b * sh.B + a) * sh.Hq + h) * topk : nullptr;
   const int Kp = min(topk, P);
-  const float* row = scores + ((size_t)head * sh.rows_max + r) * sh.max_pages;
-  const int p_first = tid * E;
   const int nmine = max(0, min(E, P - p_first));   // pages of this thread that exist
-
   uint32_t key[E];
-  if (p_first + E <= P && (sh.max_pages & 3) == 0) {
 #pragma unroll
-    for (int i = 0; i < E; i += 4) {
-      const float4 v = *reinterpret_cast<const float4*>(row + p_first + i);
-      key[i] = order_key(v.x);
-      key[i + 1] = order_key(v.y);
-      key[i + 2] = order_key(v.z);
-      key[i + 3] = order_key(v.w);
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < E; ++i) key[i] = i < nmine ? order_key(row[p_first + i]) : 0u;
-  }
+  for (int i = 0; i < E; ++i) key[i] = i < nmine ? order_key(raw[i]) : 0u;
   for (int w = tid; w < WORDS; w += 256) rowbits[w] = 0u;
-
-  // Row 0 of every (sequence, head) also gathers the head's active query rows into the dense
-  // buffer the attention kernel reads; the loads are issued here and stored after the select,
-  // so the gather rides along with the radix passes instead of following them.
-  constexpr int QV = 4;                       // 16-byte vectors per thread per sweep
-  const bool gather = out.prep.entries != nullptr && r == 0;
-  const int vpr = sh.d / 8;
-  uint4 qv[QV];
-  if (gather) {
-    const bf16_t* q = (const bf16_t*)out.q;
-#pragma unroll
-    for (int k = 0; k < QV; ++k) {
-      const int v = tid + 256 * k;
-      qv[k] = make_uint4(0u, 0u, 0u, 0u);
-      if (v < M * vpr) {
-        const int rr = v / vpr, cv = v % vpr;
-        const int tok = out.active_idx[(size_t)b * sh.B + rr / sh.G];
-        if ((unsigned)tok < (unsigned)sh.B)
-          qv[k] = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + rr % sh.G) * sh.d)[cv];
-      }
-    }
-  }
 
   const bool all = Kp >= P;
   uint32_t prefix = 0u, pmask = 0u;
   int need = Kp;
+  bool ties_cut = true;   // false once it is known that every key equal to the K-th is picked
   if (!all) {
     // highest differing bit of the row's keys
     uint32_t lo = 0xFFFFFFFFu, hi = 0u;
@@ -320,15 +336,13 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
         lo = min(lo, key[i]);
         hi = max(hi, key[i]);
       }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      lo = min(lo, (uint32_t)__shfl_xor((int)lo, o, 64));
-      hi = max(hi, (uint32_t)__shfl_xor((int)hi, o, 64));
-    }
+    lo = wave_min_u32(lo);
+    hi = wave_max_u32(hi);
     if ((tid & 63) == 0) {
       s_lo[tid >> 6] = lo;
       s_hi[tid >> 6] = hi;
     }
+    if (tid == 0) s_ncand = 0;
     __syncthreads();
     lo = min(min(s_lo[0], s_lo[1]), min(s_lo[2], s_lo[3]));
     hi = max(max(s_hi[0], s_hi[1]), max(s_hi[2], s_hi[3]));
@@ -344,14 +358,64 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
         for (int i = 0; i < E; ++i)
           if (i < nmine && (key[i] & pmask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1u);
         __syncthreads();
-        if (tid < 64) find_bucket_wave0(hist, need, &s_bucket, &s_need);
+        if (tid < 64) find_bucket_wave0(hist, need, &s_bucket, &s_need, &s_count);
         __syncthreads();
         // bits of the digit that lie above bit hb (only when hb < 7) are common to all keys
         const uint32_t dmask = 0xFFu << shift;
         prefix = (prefix & ~dmask) | (s_bucket << shift);
         pmask |= dmask;
         need = s_need;
-        if (shift == 0) break;
+        const int count = s_count;
+        if (shift == 0) {
+          ties_cut = count != need;
+          break;
+        }
+        if (count <= kRankMax) {
+          // the K-th key is the need-th largest of `count` candidates: rank them directly.
+          // Candidates are packed wavefront by wavefront (one LDS atomic each); their order
+          // in the array does not matter to the ranks.
+          int mine_n = 0;
+#pragma unroll
+          for (int i = 0; i < E; ++i) mine_n += i < nmine && (key[i] & pmask) == prefix;
+          const int incl = wave_inclusive_scan(mine_n);
+          int wbase = 0;
+          if ((tid & 63) == 63) wbase = atomicAdd(&s_ncand, incl);
+          wbase = __builtin_amdgcn_readlane(wbase, 63);
+          int at = wbase + incl - mine_n;
+#pragma unroll
+          for (int i = 0; i < E; ++i)
+            if (i < nmine && (key[i] & pmask) == prefix) cand[at++] = key[i];
+          // pad to a whole number of 16-candidate steps with keys that rank below everything
+          if (tid < 16 && count + tid < kRankMax) cand[count + tid] = 0u;
+          __syncthreads();
+          if (tid < count) {
+            const uint32_t mine = cand[tid];
+            int gt = 0, ge = 0;
+            for (int u = 0; u < count; u += 16) {
+              uint4 c4[4];
+#pragma unroll
+              for (int k = 0; k < 4; ++k) c4[k] = *reinterpret_cast<const uint4*>(&cand[u + 4 * k]);
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+                gt += (c4[k].x > mine) + (c4[k].y > mine) + (c4[k].z > mine) + (c4[k].w > mine);
+                ge += (c4[k].x >= mine) + (c4[k].y >= mine) + (c4[k].z >= mine) + (c4[k].w >= mine);
+              }
+            }
+            // the padding keys (0) count as ">= mine" only for a key that is 0 itself
+            if (mine == 0u) ge -= ((count + 15) & ~15) - count;
+            if (gt < need && need <= ge) {   // every thread that holds the K-th value writes the same
+              s_kth = mine;
+              s_need = need - gt;
+              s_count = ge - gt;
+            }
+          }
+          __syncthreads();
+          prefix = s_kth;
+          pmask = 0xFFFFFFFFu;
+          need = s_need;
+          ties_cut = s_count != need;
+          break;
+        }
       }
     } else {
       prefix = hi;          // every key is the same: ties by page order
@@ -369,9 +433,10 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     my_eq += in && !all && key[i] == prefix;
   }
   int tot_eq;
-  int eq_rank = block_exclusive_scan(my_eq, scan, &tot_eq);
+  int eq_rank = 0;   // block-uniform branch: ties_cut derives from LDS values every thread read
+  if (ties_cut) eq_rank = block_exclusive_scan(my_eq, scan, &tot_eq);
   int pos = 0, tot_sel = 0;
-  if (tk) pos = block_exclusive_scan(my_gt + max(0, min(my_eq, need - eq_rank)), scan, &tot_sel);
+  if (tk) pos = block_exclusive_scan(my_gt + (ties_cut ? max(0, min(my_eq, need - eq_rank)) : my_eq), scan, &tot_sel);
   uint32_t bits[(E + 31) / 32];
 #pragma unroll
   for (int w = 0; w < (E + 31) / 32; ++w) bits[w] = 0u;
@@ -380,7 +445,7 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     const bool in = i < nmine;
     bool sel = in && (all || key[i] > prefix);
     if (in && !all && key[i] == prefix) {
-      sel = eq_rank < need;
+      sel = !ties_cut || eq_rank < need;
       ++eq_rank;
     }
     if (sel) {
@@ -397,22 +462,6 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   if (tk)
     for (int k = tot_sel + tid; k < topk; k += 256) tk[k] = -1;
   __syncthreads();
-  if (gather) {
-    const bf16_t* q = (const bf16_t*)out.q;
-    uint4* dst = reinterpret_cast<uint4*>(out.prep.q_act + (size_t)head * sh.rows_max * sh.d);
-#pragma unroll
-    for (int k = 0; k < QV; ++k)
-      if (tid + 256 * k < M * vpr) dst[tid + 256 * k] = qv[k];
-    for (int v = tid + 256 * QV; v < M * vpr; v += 256) {   // more than QV*256 vectors: the rest, plainly
-      const int rr = v / vpr, cv = v % vpr;
-      const int tok = out.active_idx[(size_t)b * sh.B + rr / sh.G];
-      uint4 val = make_uint4(0u, 0u, 0u, 0u);
-      if ((unsigned)tok < (unsigned)sh.B)
-        val = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + rr % sh.G) * sh.d)[cv];
-      dst[v] = val;
-    }
-  }
-
   // ---- hand-over: the last row of this (sequence, head) builds the union.
   // The row bitmap travels in agent-scope atomic stores (written through to memory, past the
   // per-die L2 slices); ordering is "my stores have completed (wait count zero), then my
@@ -435,8 +484,6 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   // the set bits below it in the word: no serial walk, stores ascend with the thread id.
   const int wordsP = (P + 31) / 32;
   int32_t* sel = out.sel_pages + (size_t)head * out.cap;
-  const int base = kv.page_indptr[b];
-  const int L = kv.seq_lens[b];
   int32_t* ent = out.prep.entries ? out.prep.entries + (size_t)head * sh.max_pages : nullptr;
   __shared__ int wordbase[WORDS];
   for (int w = tid; w < WORDS; w += 256) rowbits[w] = 0u;
@@ -448,25 +495,29 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   __syncthreads();
   const uint32_t* maps = out.rowmaps + (size_t)head * sh.rows_max * words;
   {
-    // 16 independent loads at a time (a loop of load-then-use would pay one memory latency per
-    // iteration).  Plain loads: they cannot see stale data, since each cache line of the row
-    // bitmaps has exactly one writer in this launch and no reader before this point, the
-    // caches were invalidated when the launch began, and the writer's stores went through to
-    // memory (agent scope) before its ticket was drawn.
-    const int count = M * wordsP;
-    for (int i0 = tid; i0 < count; i0 += 256 * 16) {
-      uint32_t v[16];
+    // Thread t ORs bitmap word (t mod nw) of every `groups`-th row in registers, 16 independent
+    // loads at a time (a loop of load-then-use would pay one memory latency per iteration),
+    // and only the per-thread results meet in LDS.  Plain loads: they cannot see stale data,
+    // since each cache line of the row bitmaps has exactly one writer in this launch and no
+    // reader before this point, the caches were invalidated when the launch began, and the
+    // writer's stores went through to memory (agent scope) before its ticket was drawn.
+    for (int w0 = 0; w0 < wordsP; w0 += 256) {
+      const int nw = min(256, wordsP - w0);
+      const int groups = 256 / nw;
+      const int ww = w0 + tid % nw, rg = tid / nw;
+      if (rg < groups) {
+        uint32_t acc = 0u;
+        for (int r0 = rg; r0 < M; r0 += groups * 16) {
+          uint32_t v[16];
 #pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        const int idx = i0 + 256 * k;
-        const int rr = idx / wordsP, ww = idx - rr * wordsP;
-        v[k] = idx < count ? maps[(size_t)rr * words + ww] : 0u;
-      }
+          for (int k = 0; k < 16; ++k) {
+            const int rr = r0 + groups * k;
+            v[k] = maps[(size_t)min(rr, M - 1) * words + ww];
+          }
 #pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        const int idx = i0 + 256 * k;
-        const int rr = idx / wordsP, ww = idx - rr * wordsP;
-        if (v[k]) atomicOr(&rowbits[ww], v[k]);
+          for (int k = 0; k < 16; ++k) acc |= (r0 + groups * k < M) ? v[k] : 0u;
+        }
+        if (acc) atomicOr(&rowbits[ww], acc);
       }
     }
   }
@@ -481,6 +532,9 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     base_out += total;
   }
   __syncthreads();
+  // Every load of this thread has landed by now; saying so keeps the stores below from each
+  // waiting for the one before it (loads and stores share one in-order counter).
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
 #pragma unroll
   for (int i = 0; i < E; ++i) {
     const int page = tid + 256 * i;
@@ -549,7 +603,7 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
   out.prep = prep ? *prep : AttnPrepared{nullptr, nullptr, nullptr, nullptr};
   out.q = q;
   out.active_idx = active_idx;
-  dim3 grid(sh.rows_max, sh.Hkv, batch);
+  dim3 grid(sh.rows_max + 1, sh.Hkv, batch);   // + the query-gather workgroup
   const int pages = max_seq_pages < sh.max_pages ? max_seq_pages : sh.max_pages;
   if (pages <= 256 * 8)
     select_pages_kernel<8><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
