@@ -242,12 +242,13 @@ __device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need
 
 // Per-query top pages by radix select, register resident (thread t owns the E consecutive
 // pages [t*E, t*E+E); P <= 256*E), fused with the union and the hand-over described above.
-// The radix starts at the highest bit in which the row's keys differ (a block min/max finds
-// it), so the first histogram is already spread over many buckets instead of piling every
-// key onto the few exponent patterns the scores share.  As soon as the bucket that holds the
+// The radix runs on keys relative to the row's smallest key and starts at the highest bit of
+// the row's largest one (a block min/max finds both), so the first histogram is already
+// spread over many buckets instead of piling every key onto the few exponent patterns the
+// scores share.  As soon as the bucket that holds the
 // K-th key has at most kRankMax keys, those are copied to LDS and ranked against each other
 // directly (one thread per candidate), which replaces the remaining histogram passes.
-constexpr int kRankMax = 256;
+constexpr int kRankMax = 64;
 template <int E>
 __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
                                                            const float* __restrict__ scores, int topk, SelectOut out) {
@@ -346,11 +347,17 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     __syncthreads();
     lo = min(min(s_lo[0], s_lo[1]), min(s_lo[2], s_lo[3]));
     hi = max(max(s_hi[0], s_hi[1]), max(s_hi[2], s_hi[3]));
-    const uint32_t diff = lo ^ hi;
+    // Keys are taken relative to the row minimum from here on (order is unchanged): the
+    // first digit then resolves the row's actual range into 128..256 buckets wherever that
+    // range lies, instead of splitting at whatever power of two happens to fall inside it.
+#pragma unroll
+    for (int i = 0; i < E; ++i) key[i] -= lo;   // entries past the row's pages are never looked at
+    hi -= lo;
+    const uint32_t diff = hi;
     if (diff != 0u) {
-      const int hb = 31 - __clz((int)diff);          // keys agree above bit hb
+      const int hb = 31 - __clz((int)diff);          // no key has a bit above hb
       pmask = hb >= 31 ? 0u : ~((2u << hb) - 1u);
-      prefix = hi & pmask;
+      prefix = 0u;
       for (int shift = max(hb - 7, 0);; shift = max(shift - 8, 0)) {
         hist[tid] = 0u;
         __syncthreads();
@@ -418,7 +425,7 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
         }
       }
     } else {
-      prefix = hi;          // every key is the same: ties by page order
+      prefix = 0u;          // every key is the same: ties by page order
       pmask = 0xFFFFFFFFu;
     }
   } else {
@@ -535,20 +542,24 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   // Every load of this thread has landed by now; saying so keeps the stores below from each
   // waiting for the one before it (loads and stores share one in-order counter).
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
+  uint32_t wd[E];
+  int wb[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) {   // all LDS reads first: one latency, not one per page
+    wd[i] = rowbits[(tid + 256 * i) >> 5];
+    wb[i] = wordbase[(tid + 256 * i) >> 5];
+  }
 #pragma unroll
   for (int i = 0; i < E; ++i) {
     const int page = tid + 256 * i;
-    if (page < P) {
-      const uint32_t word = rowbits[page >> 5];
-      if ((word >> (page & 31)) & 1u) {
-        const int at = wordbase[page >> 5] + __popc(word & ((1u << (page & 31)) - 1u));
-        if (at < out.cap) {
-          sel[at] = page;
-          if (ent) {
-            const int nv = max(0, min(sh.g, L - page * sh.g));
-            const int ph = phys[i];
-            ent[at] = ((unsigned)ph < (unsigned)kv.num_pages && ph < (1 << kEntryShift)) ? (ph | (nv << kEntryShift)) : 0;
-          }
+    if (page < P && ((wd[i] >> (page & 31)) & 1u)) {
+      const int at = wb[i] + __popc(wd[i] & ((1u << (page & 31)) - 1u));
+      if (at < out.cap) {
+        sel[at] = page;
+        if (ent) {
+          const int nv = max(0, min(sh.g, L - page * sh.g));
+          const int ph = phys[i];
+          ent[at] = ((unsigned)ph < (unsigned)kv.num_pages && ph < (1 << kEntryShift)) ? (ph | (nv << kEntryShift)) : 0;
         }
       }
     }
