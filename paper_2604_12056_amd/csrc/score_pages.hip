@@ -149,41 +149,53 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
   const bool vec_ok = (sh.max_pages & 3) == 0 && p0 + 16 <= P;
   float* out_base = scores + ((size_t)b * sh.Hkv + j) * sh.rows_max * sh.max_pages;
 
-  for (int r0 = 0; r0 < M; r0 += 16) {
-    const int r = r0 + l16;
-    uint4 raw[KS];
+  // Query rows are taken kGroup row tiles at a time: the token ids of a group are fetched
+  // together, then all its query fragments, so a group costs two dependent round trips
+  // however many tiles it holds (slots past the active count hold -1 and give zero rows).
+  constexpr int kGroup = 4;
+  for (int r0 = 0; r0 < M; r0 += 16 * kGroup) {
+    int tok[kGroup];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) raw[ks] = make_uint4(0u, 0u, 0u, 0u);
-    if (r < M) {
-      const int a = r / sh.G, hg = r % sh.G;
-      const int tok = active_idx[(size_t)b * sh.B + a];
-      if ((unsigned)tok < (unsigned)sh.B) {
-        const bf16_t* qrow = q + (((size_t)b * sh.B + tok) * sh.Hq + j * sh.G + hg) * D;
+    for (int t = 0; t < kGroup; ++t) {
+      const int r = min(r0 + 16 * t + l16, M - 1);
+      tok[t] = active_idx[(size_t)b * sh.B + r / sh.G];
+    }
+    uint4 raw[kGroup][KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) raw[ks] = *reinterpret_cast<const uint4*>(qrow + ks * 32 + qd * 8);
+    for (int t = 0; t < kGroup; ++t) {
+      const int r = min(r0 + 16 * t + l16, M - 1);
+      const int tc = (unsigned)tok[t] < (unsigned)sh.B ? tok[t] : 0;
+      const bf16_t* qrow = q + (((size_t)b * sh.B + tc) * sh.Hq + j * sh.G + r % sh.G) * D;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) raw[t][ks] = *reinterpret_cast<const uint4*>(qrow + ks * 32 + qd * 8);
+    }
+#pragma unroll
+    for (int t = 0; t < kGroup; ++t) {
+      const int r = r0 + 16 * t + l16;
+      if (r0 + 16 * t >= M) break;   // uniform
+      const bool live = r < M && (unsigned)tok[t] < (unsigned)sh.B;
+      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        // per 16-bit half: all-ones where the sign bit is set
+        auto neg_mask = [](uint32_t x) { return ((x >> 15) & 0x00010001u) * 0xFFFFu; };
+        const uint4 x = live ? raw[t][ks] : make_uint4(0u, 0u, 0u, 0u);
+        const uint4 mk = make_uint4(neg_mask(x.x), neg_mask(x.y), neg_mask(x.z), neg_mask(x.w));
+        const uint4 qneg = make_uint4(x.x & mk.x, x.y & mk.y, x.z & mk.z, x.w & mk.w);
+        const uint4 qpos = make_uint4(x.x & ~mk.x, x.y & ~mk.y, x.z & ~mk.z, x.w & ~mk.w);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amax[ks], __builtin_bit_cast(bf16x8_t, qpos), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amin[ks], __builtin_bit_cast(bf16x8_t, qneg), acc, 0, 0, 0);
       }
-    }
-    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+      // acc[e] = score of page p0 + 4*qd + e for query row r0 + 16*t + l16
+      if (r < M) {
+        float* dst = out_base + (size_t)r * sh.max_pages + p0 + 4 * qd;
+        if (vec_ok) {
+          *reinterpret_cast<f32x4_t*>(dst) = acc;
+        } else {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      // per 16-bit half: all-ones where the sign bit is set
-      auto neg_mask = [](uint32_t x) { return ((x >> 15) & 0x00010001u) * 0xFFFFu; };
-      const uint4 x = raw[ks];
-      const uint4 mk = make_uint4(neg_mask(x.x), neg_mask(x.y), neg_mask(x.z), neg_mask(x.w));
-      const uint4 qneg = make_uint4(x.x & mk.x, x.y & mk.y, x.z & mk.z, x.w & mk.w);
-      const uint4 qpos = make_uint4(x.x & ~mk.x, x.y & ~mk.y, x.z & ~mk.z, x.w & ~mk.w);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amax[ks], __builtin_bit_cast(bf16x8_t, qpos), acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amin[ks], __builtin_bit_cast(bf16x8_t, qneg), acc, 0, 0, 0);
-    }
-    // acc[e] = score of page p0 + 4*qd + e for query row r0 + l16
-    if (r < M) {
-      float* dst = out_base + (size_t)r * sh.max_pages + p0 + 4 * qd;
-      if (vec_ok) {
-        *reinterpret_cast<f32x4_t*>(dst) = acc;
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (p0 + 4 * qd + e < P) dst[e] = acc[e];
+          for (int e = 0; e < 4; ++e)
+            if (p0 + 4 * qd + e < P) dst[e] = acc[e];
+        }
       }
     }
   }

@@ -35,15 +35,27 @@ __global__ __launch_bounds__(256) void locality_select_kernel(const T* __restric
   const uint4* pb = reinterpret_cast<const uint4*>(h_prev + (size_t)row * H);
   const int nvec = H / V;
   float acc = 0.f;
-  for (int v = tid; v < nvec; v += 256) {
-    const uint4 x = pa[v], y = pb[v];
-    float fx[V], fy[V];
-    widen16(x, fx, T());
-    widen16(y, fy, T());
+  constexpr int UN = 4;   // vectors of each operand in flight per thread
+  for (int v0 = tid; v0 < nvec; v0 += 256 * UN) {
+    uint4 x[UN], y[UN];
 #pragma unroll
-    for (int e = 0; e < V; ++e) {
-      const float df = fx[e] - fy[e];
-      acc = fmaf(df, df, acc);
+    for (int k = 0; k < UN; ++k) {   // clamped, so that all loads go out before the first is used
+      const int v = min(v0 + 256 * k, nvec - 1);
+      x[k] = pa[v];
+      y[k] = pb[v];
+    }
+#pragma unroll
+    for (int k = 0; k < UN; ++k) {
+      float fx[V], fy[V];
+      widen16(x[k], fx, T());
+      widen16(y[k], fy, T());
+      float part_k = 0.f;
+#pragma unroll
+      for (int e = 0; e < V; ++e) {
+        const float df = fx[e] - fy[e];
+        part_k = fmaf(df, df, part_k);
+      }
+      acc += v0 + 256 * k < nvec ? part_k : 0.f;
     }
   }
   acc = wave_sum(acc);

@@ -227,6 +227,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, co
       po_s[k] = reinterpret_cast<const float4*>(part.o + prow * D)[c4];
     }
   }
+  // the token of this row, fetched alongside (its slot exists whatever the active count is)
+  const int tok_early = active_idx ? active_idx[(size_t)b * sh.B + min(r / sh.G, sh.B - 1)] : r / sh.G;
   int M, U;
   if (ucount) {   // prepared by the matrix-core path
     M = min(mrows[b * sh.Hkv + j], sh.rows_max);
@@ -237,8 +239,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, co
     U = sel_count ? min(sel_count[b * sh.Hkv + j], cap) : P;
   }
   if (r >= M) return;
-  const int a = r / sh.G, hg = r % sh.G;
-  const int tok = active_idx ? active_idx[(size_t)b * sh.B + a] : a;
+  const int hg = r % sh.G;
+  const int tok = tok_early;   // r < M <= B*G here, so the index above was not clamped
   if ((unsigned)tok >= (unsigned)sh.B) return;
   const int ppt = 32 / sh.g;
   const int ntiles = (U + ppt - 1) / ppt;
