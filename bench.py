@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=16, help="independent KV caches rotated over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a graph replay")
+    ap.add_argument("--warm-single-layer", action="store_true",
+                    help="also time the same steps on one layer only (its KV stays cache resident); off by default so "
+                         "that a kernel trace of the default run holds cold launches only")
     ap.add_argument("--cpu-steps", type=int, default=12, help="oracle steps timed for cpu_baseline")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: KV load and latency versus the number of active tokens "
@@ -232,6 +235,8 @@ def main():
         reps = np.sort(np.array(reps + [us_per_step]))
         spread = {"median": round(float(np.median(reps)), 3), "p10": round(float(np.percentile(reps, 10)), 3),
                   "p90": round(float(np.percentile(reps, 90)), 3), "replays": int(reps.size)}
+    warm_us = None
+    if not args.no_graph and args.warm_single_layer:
         # the same steps on ONE layer only: its KV stays in the last-level cache between steps (warm figure)
         warm_graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(warm_graph):
@@ -248,8 +253,6 @@ def main():
         torch.cuda.synchronize()
         warm_us = e0.elapsed_time(e1) * 1e3 / args.steps
         del warm_graph
-    else:
-        warm_us = None
 
     # ---- second pass over the same steps with per-kernel events on the launch stream
     L.losa_profile_enable(ctx, True)

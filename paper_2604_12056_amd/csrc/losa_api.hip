@@ -254,7 +254,8 @@ losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const v
 
 losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
                              const void* q, const int32_t* active_idx, const int32_t* active_count, int topk,
-                             int32_t* topk_out, int32_t* sel_pages, int32_t* sel_count, int cap, bool prepare_attn) {
+                             int32_t* topk_out, int32_t* sel_pages, int32_t* sel_count, int cap, bool prepare_attn,
+                             int rows_upper) {
   const AttnPrepared* prep = prepare_attn ? &ctx->prep : nullptr;
   hipError_t e;
   {
@@ -265,7 +266,7 @@ losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   if (e != hipSuccess) return hip_fail(ctx, "page_scores launch", e);
   StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
   e = launch_select_pages(st, kv, ctx->sh, batch, max_seq_pages, q, active_idx, active_count, ctx->scores, topk,
-                          topk_out, sel_pages, sel_count, cap, ctx->rowmaps, ctx->tickets, prep);
+                          topk_out, sel_pages, sel_count, cap, ctx->rowmaps, ctx->tickets, prep, rows_upper);
   if (e != hipSuccess) return hip_fail(ctx, "select_pages launch", e);
   return LOSA_OK;
 }
@@ -468,7 +469,7 @@ losa_status losa_score_pages(losa_ctx* ctx, void* stream, const losa_kv* kv, con
   const long need = worst < msp ? worst : msp;
   if (cap < need) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap %d is below the union's worst case %ld", cap, need);
   return score_pages_impl(ctx, as_stream(stream), view_of(kv), kv->batch, msp, q, active_idx, active_count,
-                          topk_pages, topk_out, sel_pages, sel_count, cap, /*prepare_attn=*/false);
+                          topk_pages, topk_out, sel_pages, sel_count, cap, /*prepare_attn=*/false, /*rows_upper=*/0);
 }
 
 losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q, const int32_t* active_idx,
@@ -528,12 +529,12 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
   if (s != LOSA_OK) return s;
   const int cap = ctx->sh.max_pages;
   const bool fuse_prepare = ctx->cfg.dtype == LOSA_BF16;   // the selection kernel also builds the attention inputs
-  s = score_pages_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, topk_pages, nullptr,
-                       ctx->sel_pages, sc, cap, fuse_prepare);
-  if (s != LOSA_OK) return s;
-  // the host knows |A| in the top-n modes, so the attention can be shaped for n*G rows
+  // the host knows |A| in the top-n modes, so selection and attention can be shaped for n*G rows
   const bool counted = mode == LOSA_SEL_TOPK || mode == LOSA_SEL_FRACTION;
   const int rows_upper = counted ? select_count(ctx, (int)mode, param) * ctx->sh.G : 0;
+  s = score_pages_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, topk_pages, nullptr,
+                       ctx->sel_pages, sc, cap, fuse_prepare, rows_upper);
+  if (s != LOSA_OK) return s;
   return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, ctx->sel_pages, sc,
                           cap, rows_upper, fuse_prepare, (float*)o_p, lse_p);
 }

@@ -222,6 +222,7 @@ struct SelectOut {
   AttnPrepared prep;    // entries == NULL: do not build the attention inputs
   const void* q;        // query tensor (for the gather into prep.q_act)
   const int32_t* active_idx;
+  bool rows_known;      // the grid has exactly one workgroup per existing row (+ the gather workgroup)
 };
 
 // Inclusive suffix scan over 256 histogram buckets by one wavefront: lane l owns buckets
@@ -274,31 +275,35 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
   const int head = b * sh.Hkv + j;
   const int p_first = tid * E;
-  // The row's scores are fetched before anything else is known: the address depends on kernel
-  // arguments only and every row of the score buffer exists, so these loads travel together
-  // with the loads of the counts below (entries past the sequence's pages are masked later).
+  // When the host knows the row count (every workgroup of the grid has a row), the row's
+  // scores are fetched before anything else: the address depends on kernel arguments only,
+  // so these loads travel together with the loads of the counts below (entries past the
+  // sequence's pages are masked later).  Otherwise they wait until the row is known to exist.
   const float* row = scores + ((size_t)head * sh.rows_max + min(r, sh.rows_max - 1)) * sh.max_pages;
   float raw[E];
-  if (p_first + E <= sh.max_pages && (sh.max_pages & 3) == 0) {
+  auto load_row = [&]() {
+    if (p_first + E <= sh.max_pages && (sh.max_pages & 3) == 0) {
 #pragma unroll
-    for (int i = 0; i < E; i += 4) {
-      const float4 v = *reinterpret_cast<const float4*>(row + p_first + i);
-      raw[i] = v.x;
-      raw[i + 1] = v.y;
-      raw[i + 2] = v.z;
-      raw[i + 3] = v.w;
+      for (int i = 0; i < E; i += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(row + p_first + i);
+        raw[i] = v.x;
+        raw[i + 1] = v.y;
+        raw[i + 2] = v.z;
+        raw[i + 3] = v.w;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < E; ++i) raw[i] = row[min(p_first + i, sh.max_pages - 1)];
     }
-  } else {
-#pragma unroll
-    for (int i = 0; i < E; ++i) raw[i] = row[min(p_first + i, sh.max_pages - 1)];
-  }
+  };
+  if (out.rows_known) load_row();
   const int n_act = min(active_count[b], sh.B);
   const int M = n_act * sh.G;
   const int base = kv.page_indptr[b];
   const int P = max(0, min(kv.page_indptr[b + 1] - base, sh.max_pages));
   const int L = kv.seq_lens[b];
 
-  if (r == sh.rows_max) {
+  if (r == (int)gridDim.x - 1) {
     // The extra workgroup of every (sequence, head) gathers the head's active query rows into
     // the dense buffer the attention kernel reads, off the path of the selection.  Indices are
     // clamped so that every load can be issued before the one it depends on has been checked.
@@ -326,6 +331,7 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     return;
   }
   if (r >= M) return;
+  if (!out.rows_known) load_row();
   const int words = (sh.max_pages + 31) / 32;
   const int a = r / sh.G, h = j * sh.G + r % sh.G;
   int32_t* tk = out.topk_out ? out.topk_out + (((size_t)b * sh.B + a) * sh.Hq + h) * topk : nullptr;
@@ -614,7 +620,7 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
                                const void* q, const int32_t* active_idx, const int32_t* active_count,
                                const float* scores, int topk, int32_t* topk_out, int32_t* sel_pages,
                                int32_t* sel_count, int cap, uint32_t* rowmaps, int32_t* tickets,
-                               const AttnPrepared* prep) {
+                               const AttnPrepared* prep, int rows_hint) {
   if (batch <= 0) return hipSuccess;
   SelectOut out;
   out.topk_out = topk_out;
@@ -626,7 +632,10 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
   out.prep = prep ? *prep : AttnPrepared{nullptr, nullptr, nullptr, nullptr};
   out.q = q;
   out.active_idx = active_idx;
-  dim3 grid(sh.rows_max + 1, sh.Hkv, batch);   // + the query-gather workgroup
+  out.rows_known = rows_hint >= 1;
+  // rows_hint: an upper bound on |A| * G the host happens to know (0: none); rows past it get no workgroup
+  const int rows = rows_hint >= 1 && rows_hint < sh.rows_max ? rows_hint : sh.rows_max;
+  dim3 grid(rows + 1, sh.Hkv, batch);   // + the query-gather workgroup
   const int pages = max_seq_pages < sh.max_pages ? max_seq_pages : sh.max_pages;
   if (pages <= 256 * 8)
     select_pages_kernel<8><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
