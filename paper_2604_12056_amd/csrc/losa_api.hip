@@ -277,7 +277,8 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
                              bool prepared, float* o_p, float* lse_p) {
   const int upper = sel_pages ? (cap < max_seq_pages ? cap : max_seq_pages) : max_seq_pages;
   const bool mfma = ctx->cfg.dtype == LOSA_BF16;
-  if (rows_upper < 1 || rows_upper > ctx->sh.rows_max) rows_upper = ctx->sh.rows_max;
+  const bool hinted = rows_upper >= 1 && rows_upper <= ctx->sh.rows_max;
+  if (!hinted) rows_upper = ctx->sh.rows_max;
   // matrix-core kernel: up to 64 rows ride in one workgroup; more rows -> groups of 4 x 64 rows
   const int row_groups = mfma ? (rows_upper <= 64 ? 1 : (ctx->sh.rows_max + 255) / 256) : (ctx->sh.rows_max + 31) / 32;
   const int nchunk = pick_nchunk(ctx, batch, upper, mfma ? row_groups : 1);
@@ -299,7 +300,7 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
   StageTimer timer(ctx, st, LOSA_STAGE_MERGE);
   e = launch_attn_merge(st, kv, ctx->sh, batch, active_idx, active_count, sel_count, cap, nchunk,
-                        mfma ? &ctx->prep : nullptr, ctx->part, o_p, lse_p);
+                        mfma ? &ctx->prep : nullptr, ctx->part, o_p, lse_p, hinted ? rows_upper : 0);
   if (e != hipSuccess) return hip_fail(ctx, "attn_merge launch", e);
   return LOSA_OK;
 }

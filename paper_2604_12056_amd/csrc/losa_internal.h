@@ -81,7 +81,7 @@ hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, i
 hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch,
                              const int32_t* active_idx, const int32_t* active_count,
                              const int32_t* sel_count, int cap, int nchunk, const AttnPrepared* prep,
-                             const Partials& part, float* o_p, float* lse_p);
+                             const Partials& part, float* o_p, float* lse_p, int rows_hint);
 
 // ---- block_merge.hip
 hipError_t launch_block_merge(hipStream_t st, int dtype, const Shape& sh, int batch, const void* q, const void* k_b,

@@ -124,16 +124,18 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
                                                                const int32_t* __restrict__ active_idx,
                                                                const int32_t* __restrict__ active_count,
                                                                float* __restrict__ scores, ScoreAux aux) {
+  const int bx = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
   constexpr int KS = D / 32;
-  const int b = blockIdx.z, j = blockIdx.y, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, qd = lane >> 4;
   const int base = kv.page_indptr[b];
   const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
-  const int p0 = blockIdx.x * 64 + wave * 16;
+  const int p0 = bx * 64 + wave * 16;
   const int M = min(active_count[b], sh.B) * sh.G;
-  if (blockIdx.x == 0 && tid == 0) aux.reset(b * sh.Hkv + j, M);
-  if (p0 >= P) return;
+  if (bx == 0 && tid == 0) aux.reset(b * sh.Hkv + j, M);
+  if (bx * 64 >= P) return;   // whole workgroup
   if (M <= 0) return;
+  const bool live = p0 < P;   // a wavefront without pages still helps staging and keeps the barriers
 
   // A operands: metadata rows of page p0 + l16 (a valid page is read for lanes past P, never stored)
   const int pg = min(p0 + l16, P - 1);
@@ -149,46 +151,62 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
   const bool vec_ok = (sh.max_pages & 3) == 0 && p0 + 16 <= P;
   float* out_base = scores + ((size_t)b * sh.Hkv + j) * sh.rows_max * sh.max_pages;
 
-  // Query rows are taken kGroup row tiles at a time: the token ids of a group are fetched
-  // together, then all its query fragments, so a group costs two dependent round trips
-  // however many tiles it holds (slots past the active count hold -1 and give zero rows).
-  constexpr int kGroup = 4;
-  for (int r0 = 0; r0 < M; r0 += 16 * kGroup) {
-    int tok[kGroup];
+  // Query rows go through LDS, kRows at a time, so that the four wavefronts (64 pages) fetch
+  // each row once instead of once per wavefront.  A row is D bfloat16 plus 16 bytes of padding:
+  // the 16 lanes that read the same 16-byte column of 16 consecutive rows then fall on
+  // different banks.
+  constexpr int kRows = 128, VPR = D / 8, STRIDE = D * 2 + 16;   // bytes
+  __shared__ __attribute__((aligned(16))) unsigned char qs[kRows * STRIDE];
+  for (int r0 = 0; r0 < M; r0 += kRows) {
+    const int nrows = min(kRows, M - r0);
+    if (r0 > 0) __syncthreads();   // everyone is done reading the previous chunk
+    {
+      // staging: thread -> (row, 16-byte vector); token ids first, then all the row loads
+      constexpr int PER = kRows * VPR / 256;
+      int tok[PER];
 #pragma unroll
-    for (int t = 0; t < kGroup; ++t) {
-      const int r = min(r0 + 16 * t + l16, M - 1);
-      tok[t] = active_idx[(size_t)b * sh.B + r / sh.G];
+      for (int k = 0; k < PER; ++k) {
+        const int rr = min((tid + 256 * k) / VPR, nrows - 1);
+        tok[k] = active_idx[(size_t)b * sh.B + (r0 + rr) / sh.G];
+      }
+      uint4 v[PER];
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        const int rr = min((tid + 256 * k) / VPR, nrows - 1), cv = (tid + 256 * k) % VPR;
+        const int tc = (unsigned)tok[k] < (unsigned)sh.B ? tok[k] : 0;
+        v[k] = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tc) * sh.Hq + j * sh.G + (r0 + rr) % sh.G) * D)[cv];
+      }
+#pragma unroll
+      for (int k = 0; k < PER; ++k) {
+        const int rr = (tid + 256 * k) / VPR, cv = (tid + 256 * k) % VPR;
+        if (rr < nrows)
+          *reinterpret_cast<uint4*>(qs + rr * STRIDE + cv * 16) =
+              (unsigned)tok[k] < (unsigned)sh.B ? v[k] : make_uint4(0u, 0u, 0u, 0u);
+      }
     }
-    uint4 raw[kGroup][KS];
+    __syncthreads();
+    if (!live) continue;
+    for (int t0 = 0; t0 < nrows; t0 += 16) {
+      const int rr = t0 + l16;           // row of this lane inside the chunk (may be past nrows: masked below)
+      uint4 raw[KS];
 #pragma unroll
-    for (int t = 0; t < kGroup; ++t) {
-      const int r = min(r0 + 16 * t + l16, M - 1);
-      const int tc = (unsigned)tok[t] < (unsigned)sh.B ? tok[t] : 0;
-      const bf16_t* qrow = q + (((size_t)b * sh.B + tc) * sh.Hq + j * sh.G + r % sh.G) * D;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) raw[t][ks] = *reinterpret_cast<const uint4*>(qrow + ks * 32 + qd * 8);
-    }
-#pragma unroll
-    for (int t = 0; t < kGroup; ++t) {
-      const int r = r0 + 16 * t + l16;
-      if (r0 + 16 * t >= M) break;   // uniform
-      const bool live = r < M && (unsigned)tok[t] < (unsigned)sh.B;
+      for (int ks = 0; ks < KS; ++ks)
+        raw[ks] = *reinterpret_cast<const uint4*>(qs + min(rr, nrows - 1) * STRIDE + ks * 64 + qd * 16);
       f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         // per 16-bit half: all-ones where the sign bit is set
         auto neg_mask = [](uint32_t x) { return ((x >> 15) & 0x00010001u) * 0xFFFFu; };
-        const uint4 x = live ? raw[t][ks] : make_uint4(0u, 0u, 0u, 0u);
+        const uint4 x = raw[ks];
         const uint4 mk = make_uint4(neg_mask(x.x), neg_mask(x.y), neg_mask(x.z), neg_mask(x.w));
         const uint4 qneg = make_uint4(x.x & mk.x, x.y & mk.y, x.z & mk.z, x.w & mk.w);
         const uint4 qpos = make_uint4(x.x & ~mk.x, x.y & ~mk.y, x.z & ~mk.z, x.w & ~mk.w);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amax[ks], __builtin_bit_cast(bf16x8_t, qpos), acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amin[ks], __builtin_bit_cast(bf16x8_t, qneg), acc, 0, 0, 0);
       }
-      // acc[e] = score of page p0 + 4*qd + e for query row r0 + 16*t + l16
-      if (r < M) {
-        float* dst = out_base + (size_t)r * sh.max_pages + p0 + 4 * qd;
+      // acc[e] = score of page p0 + 4*qd + e for query row r0 + t0 + l16
+      if (rr < nrows) {
+        float* dst = out_base + (size_t)(r0 + rr) * sh.max_pages + p0 + 4 * qd;
         if (vec_ok) {
           *reinterpret_cast<f32x4_t*>(dst) = acc;
         } else {

@@ -342,9 +342,11 @@ hipError_t launch_attn_generic(hipStream_t st, int dtype, const KvView& kv, cons
 
 hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const int32_t* active_idx,
                              const int32_t* active_count, const int32_t* sel_count, int cap, int nchunk,
-                             const AttnPrepared* prep, const Partials& part, float* o_p, float* lse_p) {
+                             const AttnPrepared* prep, const Partials& part, float* o_p, float* lse_p, int rows_hint) {
   if (batch <= 0) return hipSuccess;
-  dim3 grid(sh.rows_max, sh.Hkv, batch);
+  // rows_hint: an upper bound on the active rows per KV head the host happens to know (0: none);
+  // rows past it get no workgroup (they would only fetch partials speculatively and exit)
+  dim3 grid(rows_hint >= 1 && rows_hint < sh.rows_max ? rows_hint : sh.rows_max, sh.Hkv, batch);
   const int32_t* uc = prep ? prep->ucount : nullptr;
   const int32_t* mr = prep ? prep->mrows : nullptr;
   if (sh.d == 128) {
