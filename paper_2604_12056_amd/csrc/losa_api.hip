@@ -47,6 +47,7 @@ struct losa_ctx {
   Partials part;
   long part_items;
   long target_workgroups;   // attention workgroups aimed at per launch
+  bool rank_in_scores;      // losa_step lets the scoring kernel rank the locality scores (env LOSA_RANK_IN_SCORES=0: off)
   AttnPrepared prep;
   char err[256];
   // measurement hooks
@@ -218,27 +219,36 @@ int select_count(const losa_ctx* ctx, int mode, float param) {
   return n < 1 ? 1 : (n > B ? B : n);
 }
 
+// Checks (mode, param) and turns them into what the kernels take: a count n or a threshold tau.
+losa_status parse_select(losa_ctx* ctx, int mode, float param, int* n, float* tau) {
+  *n = 0;
+  *tau = 0.f;
+  if (mode == LOSA_SEL_TOPK) {
+    if (!(param >= 0.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "top-k parameter must be >= 0");
+    *n = select_count(ctx, mode, param);
+  } else if (mode == LOSA_SEL_FRACTION) {
+    if (!(param >= 0.f && param <= 1.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "fraction must be in [0,1]");
+    *n = select_count(ctx, mode, param);
+  } else if (mode == LOSA_SEL_THRESHOLD) {
+    if (isnan(param)) return fail(ctx, LOSA_ERR_INVALID_ARG, "threshold is NaN");
+    *tau = param;
+  } else if (mode == LOSA_SEL_MASS) {
+    if (!(param >= 0.f && param <= 1.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "mass fraction must be in [0,1]");
+    *tau = param;
+  } else {
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "unknown select mode %d", mode);
+  }
+  return LOSA_OK;
+}
+
 losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const void* h_cur, const void* h_prev,
                                int mode, float param, float* delta, uint8_t* mask, int32_t* active_idx,
                                int32_t* active_count) {
   const int B = ctx->sh.B;
   int n = 0;
   float tau = 0.f;
-  if (mode == LOSA_SEL_TOPK) {
-    if (!(param >= 0.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "top-k parameter must be >= 0");
-    n = select_count(ctx, mode, param);
-  } else if (mode == LOSA_SEL_FRACTION) {
-    if (!(param >= 0.f && param <= 1.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "fraction must be in [0,1]");
-    n = select_count(ctx, mode, param);
-  } else if (mode == LOSA_SEL_THRESHOLD) {
-    if (isnan(param)) return fail(ctx, LOSA_ERR_INVALID_ARG, "threshold is NaN");
-    tau = param;
-  } else if (mode == LOSA_SEL_MASS) {
-    if (!(param >= 0.f && param <= 1.f)) return fail(ctx, LOSA_ERR_INVALID_ARG, "mass fraction must be in [0,1]");
-    tau = param;
-  } else {
-    return fail(ctx, LOSA_ERR_INVALID_ARG, "unknown select mode %d", mode);
-  }
+  const losa_status ps = parse_select(ctx, mode, param, &n, &tau);
+  if (ps != LOSA_OK) return ps;
   StageTimer timer(ctx, st, LOSA_STAGE_LOCALITY);
   hipError_t e;
   if (!ctx->seq_tickets_clean) {   // first use: the ticket counters must start at zero; the kernel leaves them so
@@ -255,13 +265,13 @@ losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const v
 losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
                              const void* q, const int32_t* active_idx, const int32_t* active_count, int topk,
                              int32_t* topk_out, int32_t* sel_pages, int32_t* sel_count, int cap, bool prepare_attn,
-                             int rows_upper) {
+                             int rows_upper, const InKernelRanking* ranking = nullptr) {
   const AttnPrepared* prep = prepare_attn ? &ctx->prep : nullptr;
   hipError_t e;
   {
     StageTimer timer(ctx, st, LOSA_STAGE_SCORE);
     e = launch_page_scores(st, ctx->cfg.dtype, kv, ctx->sh, batch, max_seq_pages, q, active_idx, active_count,
-                           ctx->scores, ctx->tickets, sel_count, prep);
+                           ctx->scores, ctx->tickets, sel_count, prep, ranking);
   }
   if (e != hipSuccess) return hip_fail(ctx, "page_scores launch", e);
   StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
@@ -354,6 +364,8 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   ctx->part.l = (float*)(base + L.pl);
   ctx->part_items = L.part_items;
   ctx->target_workgroups = kTargetWorkgroups;
+  ctx->rank_in_scores = true;
+  if (const char* env = getenv("LOSA_RANK_IN_SCORES")) ctx->rank_in_scores = atoi(env) != 0;
   if (const char* env = getenv("LOSA_ATTN_WORKGROUPS")) {   // tuning knob: one workgroup per CU by default
     const long v = atol(env);
     if (v >= 1 && v <= L.part_items) ctx->target_workgroups = v;
@@ -525,16 +537,30 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
                 ctx->cfg.max_topk_pages);
   uint8_t* mk = mask ? mask : ctx->mask;
   int32_t* sc = sel_count ? sel_count : ctx->sel_count;
-  s = select_active_impl(ctx, st, kv->batch, h_cur, h_prev, (int)mode, param, ctx->delta, mk, ctx->active_idx,
-                         ctx->active_count);
-  if (s != LOSA_OK) return s;
+  // Where the scoring kernel can rank the locality scores itself, the locality launch only
+  // computes them: its end-of-kernel hand-over (store, wait, ticket, reload, rank) drops out
+  // of the step's chain of dependent launches.
+  InKernelRanking ranking{ctx->delta, (int)mode, 0, 0.f, mk, ctx->active_idx, ctx->active_count};
+  const bool rank_in_scores = ctx->rank_in_scores && ctx->cfg.dtype == LOSA_BF16 && ctx->sh.B <= 256 &&
+                              mode != LOSA_SEL_MASS;
+  if (rank_in_scores) {
+    s = parse_select(ctx, (int)mode, param, &ranking.n, &ranking.tau);
+    if (s != LOSA_OK) return s;
+    StageTimer timer(ctx, st, LOSA_STAGE_LOCALITY);
+    hipError_t e = launch_locality_delta(st, ctx->cfg.dtype, h_cur, h_prev, kv->batch, ctx->sh.B, ctx->sh.H, ctx->delta);
+    if (e != hipSuccess) return hip_fail(ctx, "locality_delta launch", e);
+  } else {
+    s = select_active_impl(ctx, st, kv->batch, h_cur, h_prev, (int)mode, param, ctx->delta, mk, ctx->active_idx,
+                           ctx->active_count);
+    if (s != LOSA_OK) return s;
+  }
   const int cap = ctx->sh.max_pages;
   const bool fuse_prepare = ctx->cfg.dtype == LOSA_BF16;   // the selection kernel also builds the attention inputs
   // the host knows |A| in the top-n modes, so selection and attention can be shaped for n*G rows
   const bool counted = mode == LOSA_SEL_TOPK || mode == LOSA_SEL_FRACTION;
   const int rows_upper = counted ? select_count(ctx, (int)mode, param) * ctx->sh.G : 0;
   s = score_pages_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, topk_pages, nullptr,
-                       ctx->sel_pages, sc, cap, fuse_prepare, rows_upper);
+                       ctx->sel_pages, sc, cap, fuse_prepare, rows_upper, rank_in_scores ? &ranking : nullptr);
   if (s != LOSA_OK) return s;
   return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, ctx->sel_pages, sc,
                           cap, rows_upper, fuse_prepare, (float*)o_p, lse_p);

@@ -49,6 +49,9 @@ struct AttnPrepared {
 hipError_t launch_locality_select(hipStream_t st, int dtype, const void* h_cur, const void* h_prev, int batch, int B,
                                   int H, int mode, int n, float tau, float* delta, uint8_t* mask, int32_t* active_idx,
                                   int32_t* active_count, int32_t* tickets);
+// Locality scores only (no ranking): for the step whose scoring kernel ranks them itself.
+hipError_t launch_locality_delta(hipStream_t st, int dtype, const void* h_cur, const void* h_prev, int batch, int B,
+                                 int H, float* delta);
 
 // ---- page_bounds.hip
 hipError_t launch_page_bounds(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
@@ -56,9 +59,21 @@ hipError_t launch_page_bounds(hipStream_t st, int dtype, const KvView& kv, const
 
 // ---- score_pages.hip
 constexpr int kMaxSelectPages = 256 * 64;   // pages per sequence the register-resident top-k handles
+// ranking != NULL (bfloat16, B <= 256, not the cumulative-mass mode): the scoring workgroups derive the
+// active set from `delta` themselves and write mask / active_idx / active_count; the active_idx /
+// active_count arguments are then outputs of this launch, not inputs.
+struct InKernelRanking {
+  const float* delta;
+  int mode, n;
+  float tau;
+  uint8_t* mask;
+  int32_t* active_idx;
+  int32_t* active_count;
+};
 hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
                               const void* q, const int32_t* active_idx, const int32_t* active_count,
-                              float* scores, int32_t* tickets, int32_t* sel_count, const AttnPrepared* prep);
+                              float* scores, int32_t* tickets, int32_t* sel_count, const AttnPrepared* prep,
+                              const InKernelRanking* ranking);
 hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
                                const void* q, const int32_t* active_idx, const int32_t* active_count,
                                const float* scores, int topk, int32_t* topk_out, int32_t* sel_pages,

@@ -34,6 +34,22 @@ struct ScoreAux {
   }
 };
 
+// In-kernel locality pruning (paper: Methodology, Locality Pruning): when `delta` is given,
+// every scoring workgroup ranks the block's locality scores itself (B <= kRankTokens, one
+// thread per token, ranking by counting as in the stand-alone kernel) instead of reading an
+// active list some earlier launch produced, and the first workgroup of each sequence writes
+// mask / list / count out for the kernels that follow.  This replaces the hand-over at the end
+// of the locality kernel (store, wait, ticket, reload, rank) by B compares per thread here.
+constexpr int kRankTokens = 256;
+struct RankArgs {
+  const float* delta;     // [batch*B] locality scores; NULL: use the active list passed to the kernel
+  int mode, n;            // LOSA_SEL_TOPK / FRACTION (n = count) or LOSA_SEL_THRESHOLD (tau)
+  float tau;
+  uint8_t* mask;          // outputs, written by workgroup (0, 0, b)
+  int32_t* active_idx;
+  int32_t* active_count;
+};
+
 constexpr int kScorePages = 32;  // pages per workgroup in page_scores
 constexpr int kScoreRows = 32;   // query rows staged at a time
 
@@ -123,7 +139,7 @@ template <int D>
 __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape sh, const bf16_t* __restrict__ q,
                                                                const int32_t* __restrict__ active_idx,
                                                                const int32_t* __restrict__ active_count,
-                                                               float* __restrict__ scores, ScoreAux aux) {
+                                                               float* __restrict__ scores, ScoreAux aux, RankArgs ra) {
   const int bx = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
   constexpr int KS = D / 32;
   const int tid = threadIdx.x;
@@ -131,7 +147,43 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
   const int base = kv.page_indptr[b];
   const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
   const int p0 = bx * 64 + wave * 16;
-  const int M = min(active_count[b], sh.B) * sh.G;
+  __shared__ float sdelta[kRankTokens];
+  __shared__ int act_list[kRankTokens];
+  __shared__ int rscan[17];
+  const bool ranked = ra.delta != nullptr;   // uniform over the launch
+  int M;
+  if (ranked) {
+    const int B = sh.B;   // <= kRankTokens (checked by the launcher)
+    if (tid < B) sdelta[tid] = ra.delta[(size_t)b * B + tid];
+    __syncthreads();
+    int act = 0;
+    if (tid < B) {
+      const float di = sdelta[tid];
+      if (ra.mode == LOSA_SEL_THRESHOLD) {
+        act = di > ra.tau;
+      } else {
+        int rank = 0;
+        for (int k = 0; k < B; ++k) {
+          const float dk = sdelta[k];
+          rank += (dk > di) || (dk == di && k < tid);
+        }
+        act = rank < ra.n;
+      }
+    }
+    int n_act;
+    const int pos = block_exclusive_scan(act, rscan, &n_act);
+    if (act) act_list[pos] = tid;
+    if (bx == 0 && j == 0) {
+      if (tid < B) ra.mask[(size_t)b * B + tid] = (uint8_t)act;
+      if (act) ra.active_idx[(size_t)b * B + pos] = tid;
+      for (int i = n_act + tid; i < B; i += 256) ra.active_idx[(size_t)b * B + i] = -1;
+      if (tid == 0) ra.active_count[b] = n_act;
+    }
+    __syncthreads();   // act_list is read below
+    M = n_act * sh.G;
+  } else {
+    M = min(active_count[b], sh.B) * sh.G;
+  }
   if (bx == 0 && tid == 0) aux.reset(b * sh.Hkv + j, M);
   if (bx * 64 >= P) return;   // whole workgroup
   if (M <= 0) return;
@@ -167,7 +219,7 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
 #pragma unroll
       for (int k = 0; k < PER; ++k) {
         const int rr = min((tid + 256 * k) / VPR, nrows - 1);
-        tok[k] = active_idx[(size_t)b * sh.B + (r0 + rr) / sh.G];
+        tok[k] = ranked ? act_list[(r0 + rr) / sh.G] : active_idx[(size_t)b * sh.B + (r0 + rr) / sh.G];
       }
       uint4 v[PER];
 #pragma unroll
@@ -613,18 +665,24 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
 hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
                               int max_seq_pages, const void* q, const int32_t* active_idx,
                               const int32_t* active_count, float* scores, int32_t* tickets, int32_t* sel_count,
-                              const AttnPrepared* prep) {
+                              const AttnPrepared* prep, const InKernelRanking* ranking) {
   if (batch <= 0) return hipSuccess;
   ScoreAux aux{tickets, sel_count, prep ? prep->ucount : nullptr, prep ? prep->mrows : nullptr};
+  RankArgs ra{nullptr, 0, 0, 0.f, nullptr, nullptr, nullptr};
+  if (ranking) {
+    if (dtype != LOSA_BF16 || sh.B > kRankTokens || ranking->mode == LOSA_SEL_MASS) return hipErrorInvalidValue;
+    ra = RankArgs{ranking->delta, ranking->mode, ranking->n, ranking->tau, ranking->mask, ranking->active_idx,
+                  ranking->active_count};
+  }
   dim3 grid((max_seq_pages + kScorePages - 1) / kScorePages, sh.Hkv, batch);
   if (grid.x == 0) grid.x = 1;
   if (dtype == LOSA_BF16) {
     dim3 mgrid((max_seq_pages + 63) / 64, sh.Hkv, batch);
     if (mgrid.x == 0) mgrid.x = 1;
     if (sh.d == 128)
-      page_scores_mfma_kernel<128><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux);
+      page_scores_mfma_kernel<128><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux, ra);
     else
-      page_scores_mfma_kernel<64><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux);
+      page_scores_mfma_kernel<64><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux, ra);
   } else {
     if (sh.d == 128)
       page_scores_kernel<float, 128><<<grid, 256, 0, st>>>(kv, sh, (const float*)q, active_idx, active_count, scores, aux);

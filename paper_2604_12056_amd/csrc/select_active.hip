@@ -61,6 +61,10 @@ __global__ __launch_bounds__(256) void locality_select_kernel(const T* __restric
   acc = wave_sum(acc);
   if ((tid & 63) == 0) part[tid >> 6] = acc;
   __syncthreads();
+  if (mode < 0) {   // scores only: whoever ranks them runs in a later launch
+    if (tid == 0) delta[row] = (part[0] + part[1] + part[2] + part[3]) / (float)H;
+    return;
+  }
   if (tid == 0) {
     const float d = (part[0] + part[1] + part[2] + part[3]) / (float)H;
     __hip_atomic_store(&delta[row], d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -150,6 +154,12 @@ hipError_t launch_locality_select(hipStream_t st, int dtype, const void* h_cur, 
     locality_select_kernel<float><<<batch * B, 256, 0, st>>>((const float*)h_cur, (const float*)h_prev, H, B, mode, n,
                                                              tau, delta, mask, active_idx, active_count, tickets);
   return hipGetLastError();
+}
+
+hipError_t launch_locality_delta(hipStream_t st, int dtype, const void* h_cur, const void* h_prev, int batch, int B,
+                                 int H, float* delta) {
+  return launch_locality_select(st, dtype, h_cur, h_prev, batch, B, H, /*mode=*/-1, 0, 0.f, delta, nullptr, nullptr,
+                                nullptr, nullptr);
 }
 
 }  // namespace losa
