@@ -331,6 +331,18 @@ def main():
         cpu_us = (time.perf_counter() - c0) * 1e6 / n_cpu
         out["cpu_baseline"] = {"value": round(cpu_us, 1), "unit": "us", "cores": int(cores), "kind": "oracle",
                                "sample": f"sparse steps 1..{n_cpu} of layer 0 of {w.name} (numpy float64 oracle)"}
+        # the same oracle held to one thread, on fewer steps (reported beside the figure above)
+        try:
+            from threadpoolctl import threadpool_limits
+            n_one = min(4, n_cpu)
+            with threadpool_limits(limits=1):
+                c0 = time.perf_counter()
+                for t in range(1, 1 + n_one):
+                    orc.losa_step(cache, t, inp0.h[t], inp0.h[t - 1], inp0.q[t], mode, param, topk, w.B, w.Hq,
+                                  o_ref, L_ref)
+                out["cpu_baseline"]["single_thread_us"] = round((time.perf_counter() - c0) * 1e6 / n_one, 1)
+        except Exception:
+            pass
     ctx.close()
     print(json.dumps(out), flush=True)
 

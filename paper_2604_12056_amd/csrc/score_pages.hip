@@ -328,16 +328,18 @@ __device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need
 // The radix runs on keys relative to the row's smallest key and starts at the highest bit of
 // the row's largest one (a block min/max finds both), so the first histogram is already
 // spread over many buckets instead of piling every key onto the few exponent patterns the
-// scores share.  As soon as the bucket that holds the
-// K-th key has at most kRankMax keys, those are copied to LDS and ranked against each other
-// directly (one thread per candidate), which replaces the remaining histogram passes.
-constexpr int kRankMax = 64;
+// scores share.  As soon as the bucket that holds the K-th key has at most RankMax<E> keys,
+// those are copied to LDS and ranked against each other directly (one thread per candidate),
+// which replaces the remaining histogram passes.  With more keys per thread a histogram pass
+// costs more, so direct ranking pays for larger buckets.
+template <int E> struct RankMax { static constexpr int value = E >= 32 ? 256 : 64; };
 template <int E>
 __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
                                                            const float* __restrict__ scores, int topk, SelectOut out) {
   constexpr int WORDS = 256 * E / 32;
   __shared__ uint32_t hist[256];
   __shared__ uint32_t rowbits[WORDS];
+  constexpr int kRankMax = RankMax<E>::value;
   __shared__ __attribute__((aligned(16))) uint32_t cand[kRankMax];
   __shared__ uint32_t s_bucket, s_lo[4], s_hi[4], s_kth;
   __shared__ int s_need, s_last, s_count, s_ncand;
@@ -350,12 +352,20 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   // so these loads travel together with the loads of the counts below (entries past the
   // sequence's pages are masked later).  Otherwise they wait until the row is known to exist.
   const float* row = scores + ((size_t)head * sh.rows_max + min(r, sh.rows_max - 1)) * sh.max_pages;
+  // With 8 keys per thread each thread simply loads its own 32 contiguous bytes.  With 32 or 64
+  // keys per thread that pattern (lanes 128 or 256 bytes apart, every cache line revisited by
+  // 8 instructions) thrashes the 32 KiB vector cache, so the row is loaded coalesced instead
+  // (float4 number tid + 256*k) and handed to its owners through LDS afterwards (own_row).
+  constexpr bool STAGED = E >= 32;
+  extern __shared__ __attribute__((aligned(16))) float stage[];   // STAGED: 256 * (E + 4) floats
+  const bool vec_row = (sh.max_pages & 3) == 0 && (STAGED || p_first + E <= sh.max_pages);
   float raw[E];
   auto load_row = [&]() {
-    if (p_first + E <= sh.max_pages && (sh.max_pages & 3) == 0) {
+    if (vec_row) {
 #pragma unroll
       for (int i = 0; i < E; i += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(row + p_first + i);
+        const int v4 = STAGED ? min(tid + 256 * (i / 4), sh.max_pages / 4 - 1) : (p_first + i) / 4;
+        const float4 v = reinterpret_cast<const float4*>(row)[v4];
         raw[i] = v.x;
         raw[i + 1] = v.y;
         raw[i + 2] = v.z;
@@ -364,6 +374,25 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     } else {
 #pragma unroll
       for (int i = 0; i < E; ++i) raw[i] = row[min(p_first + i, sh.max_pages - 1)];
+    }
+  };
+  // STAGED: pages 4*(tid + 256k).. were loaded; afterwards raw[i] is page p_first + i.  A thread's
+  // E keys sit E + 4 floats apart in LDS, which keeps both the writes and the reads conflict free.
+  auto own_row = [&]() {
+    if (!STAGED || !vec_row) return;
+#pragma unroll
+    for (int i = 0; i < E; i += 4) {
+      const int p = 4 * (tid + 256 * (i / 4));   // first page of this float4 (p < 256 * E)
+      *reinterpret_cast<float4*>(stage + (p / E) * (E + 4) + p % E) = make_float4(raw[i], raw[i + 1], raw[i + 2], raw[i + 3]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < E; i += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(stage + tid * (E + 4) + i);
+      raw[i] = v.x;
+      raw[i + 1] = v.y;
+      raw[i + 2] = v.z;
+      raw[i + 3] = v.w;
     }
   };
   if (out.rows_known) load_row();
@@ -402,6 +431,7 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   }
   if (r >= M) return;
   if (!out.rows_known) load_row();
+  own_row();
   const int words = (sh.max_pages + 31) / 32;
   const int a = r / sh.G, h = j * sh.G + r % sh.G;
   int32_t* tk = out.topk_out ? out.topk_out + (((size_t)b * sh.B + a) * sh.Hq + h) * topk : nullptr;
@@ -713,14 +743,23 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
   const int rows = rows_hint >= 1 && rows_hint < sh.rows_max ? rows_hint : sh.rows_max;
   dim3 grid(rows + 1, sh.Hkv, batch);   // + the query-gather workgroup
   const int pages = max_seq_pages < sh.max_pages ? max_seq_pages : sh.max_pages;
-  if (pages <= 256 * 8)
+  if (pages <= 256 * 8) {
     select_pages_kernel<8><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
-  else if (pages <= 256 * 32)
-    select_pages_kernel<32><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
-  else if (pages <= kMaxSelectPages)
-    select_pages_kernel<64><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
-  else
+  } else if (pages <= 256 * 32) {
+    select_pages_kernel<32><<<grid, 256, 256 * (32 + 4) * sizeof(float), st>>>(kv, sh, active_count, scores, topk, out);
+  } else if (pages <= kMaxSelectPages) {
+    constexpr size_t lds = 256 * (64 + 4) * sizeof(float);   // above the default dynamic limit
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_pages_kernel<64>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    select_pages_kernel<64><<<grid, 256, lds, st>>>(kv, sh, active_count, scores, topk, out);
+  } else {
     return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

@@ -45,3 +45,14 @@ def test_c4_sweep_points(fraction, budget):
 
 def test_c1_full_float_mode():
     _run(synth.config(1, dtype="f32").replace(T=2, seq_lens=(8192 + 40,)), range(2))
+
+
+@pytest.mark.parametrize("pages,tail", [(3001, 5), (9001, 5), (9004, 11), (16384, 0)])
+def test_long_sequences_up_to_the_page_limit(pages, tail):
+    """Above 2048 / 8192 pages the selection kernel holds 32 / 64 keys per thread (16384 pages is
+    the limit of the interface); page counts that are not a multiple of four take its scalar
+    score loads.  A single-KV-head shape keeps the oracle quick."""
+    L = 16 * (pages - 1) + (tail if tail else 16)
+    w = synth.config(0).replace(seq_lens=(L,), topk_pages=96, T=3, name=f"C0-{pages}-pages")
+    assert w.max_pages == pages
+    _run(w, range(3))

@@ -91,6 +91,21 @@ def test_losa_step_threshold_and_mass_modes(rig):
     assert rig.near_ties <= 2
 
 
+@pytest.mark.parametrize("idx", [0, 2])
+def test_losa_step_with_ranking_in_the_locality_kernel(idx, monkeypatch):
+    """losa_step normally lets the scoring kernel rank the locality scores; blocks larger than it
+    handles, and the cumulative-mass mode, take the locality kernel's own ranking.  Forced here
+    for ordinary workloads (the switch is read when the context is created)."""
+    monkeypatch.setenv("LOSA_RANK_IN_SCORES", "0")
+    r = Rig(small_workloads()[idx])
+    try:
+        check_page_bounds(r)
+        run_steps_end_to_end(r, range(r.w.T), orc.SEL_TOPK, float(r.w.n_active), r.w.topk_pages)
+        assert r.near_ties <= 2
+    finally:
+        r.close()
+
+
 def test_budget_covering_every_page_equals_dense(rig):
     """All tokens active and K >= P: the sparse path must reproduce dense prefix attention."""
     w, blk = rig.w, rig.blk
