@@ -22,9 +22,9 @@ struct KvView {
 
 // Static problem shape, passed to kernels by value.
 struct Shape {
-  int32_t Hq, Hkv, G, d, H, g, B;
   int32_t max_pages;   // row stride of the score matrix / bitmap sizing (config.max_pages_per_seq)
   int32_t rows_max;    // B * G: rows of one KV head when every token is active
+  int32_t Hkv, Hq, G, d, H, g, B;
   float sm_scale;
 };
 

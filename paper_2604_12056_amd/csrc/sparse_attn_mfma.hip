@@ -91,7 +91,7 @@ struct MergeSlot {   // LDS image of one wavefront's state: O as [row tile][chan
 // at once when it starts: the only dependent memory round trip left before key/value data
 // flows is entries -> pages.
 template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, AttnPrepared prep, int nchunk, int nrbg,
+__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv,
                                                         Partials part, float scale_log2e) {
   constexpr int KS = D / 32;    // k-steps of the score product
   constexpr int NT = D / 16;    // channel tiles of the output
@@ -114,15 +114,25 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
   const int tstep = nchunk * wstride;           // distance between its tiles
   const int32_t* ent = prep.entries + (size_t)head * sh.max_pages;
 
-  // ---- everything below is issued before anything is waited for
-  const int U = min(prep.ucount[head], sh.max_pages);
-  const int M = min(prep.mrows[head], sh.rows_max);
+  // ---- start-up.  What gates the kernel is when the first key/value load leaves, and that
+  // needs only the counts and the page entries: they are fetched first, the exit tests follow,
+  // and the query fragments are requested next but not waited for until after the first tiles
+  // have been requested (they arrive long before the first tile does).
+  const int U_raw = prep.ucount[head], M_raw = prep.mrows[head];
   int pg_entry;
   auto fetch_entries = [&](int first_local_tile) {
     const long lp = ((long)tfirst + (long)(first_local_tile + lane / PPT) * tstep) * PPT + lane % PPT;
     pg_entry = lp < sh.max_pages ? ent[lp] : 0;   // inside the array whatever U is; checked against U at use
   };
   fetch_entries(0);
+  const int U = min(U_raw, sh.max_pages);
+  const int M = min(M_raw, sh.rows_max);
+  const int ntiles = (U + PPT - 1) / PPT;
+  // M <= 0: nothing active; chunk >= ntiles: this workgroup owns no tile; third: no rows for this
+  // wavefront in the split-rows shape (which uses no barrier)
+  if ((M <= 0) | (chunk >= ntiles) | (!SPLIT_PAGES && rb * (R * 16) >= M)) return;
+  const int ntw = tfirst < ntiles ? (ntiles - 1 - tfirst) / tstep + 1 : 0;   // this wavefront's tiles
+
   bf16x8_t qf[R][KS];
   {
     const bf16_t* qa = prep.q_act + (size_t)head * sh.rows_max * D;
@@ -134,20 +144,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
         qf[mt][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qa + (size_t)rg * D + ks * 32 + qd * 8));
     }
   }
-
-  if (M <= 0) return;
-  if (!SPLIT_PAGES && rb * (R * 16) >= M) return;   // no barrier is used in this shape
-  const int ntiles = (U + PPT - 1) / PPT;
-  if (chunk >= ntiles) return;                      // this workgroup owns no tile
-  const int ntw = tfirst < ntiles ? (ntiles - 1 - tfirst) / tstep + 1 : 0;   // this wavefront's tiles
-
-  // rows past M hold whatever the workspace held: make them zero queries
-#pragma unroll
-  for (int mt = 0; mt < R; ++mt)
-    if (rb * (R * 16) + mt * 16 + l16 >= M) {
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) qf[mt][ks] = __builtin_bit_cast(bf16x8_t, make_uint4(0u, 0u, 0u, 0u));
-    }
+  __builtin_amdgcn_sched_barrier(0);   // the query loads stay ahead of the tile loads below
 
   float m_run[R], l_run[R];
   f32x4_t o[R][NT];
@@ -345,18 +342,38 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(KvView kv, Shape sh, Att
     }
   };
 
-  // ---- main loop: NBUF tile buffers in registers, NBUF-1 tiles of lookahead.  A memory round
-  // trip costs about as much as computing two tiles and a wavefront has one wavefront per
-  // SIMD to itself, so latency is hidden by depth, not by occupancy.  Every load is issued
-  // unconditionally (see load_tile) so that the number of loads in flight at each use is a
-  // compile-time constant: a load behind a branch would force a full drain at the join.
+  // ---- main loop: NBUF tile buffers in registers, NBUF-1 tiles of lookahead (how many: see
+  // the launcher).  A wavefront has a SIMD to itself, so memory latency is hidden by its own
+  // lookahead, not by occupancy.  Every load is issued unconditionally (see load_tile) so that
+  // the number of loads in flight at each use is a compile-time constant: a load behind a
+  // branch would force a full drain at the join.
   Tile tb[NBUF];
-  for (int nb = 0; nb < ntw; nb += TPR) {
-    if (nb > 0) fetch_entries(nb);
-    decode_entries(nb);
-    const int ne = min(ntw, nb + TPR);
+  decode_entries(0);
 #pragma unroll
-    for (int k = 0; k < NBUF - 1; ++k) load_tile(tb[k], nb + k, ne);
+  for (int k = 0; k < NBUF - 1; ++k) load_tile(tb[k], k, min(ntw, TPR));
+  __builtin_amdgcn_sched_barrier(0);
+  // rows past M hold whatever the workspace held: make them zero queries (first wait for them)
+#pragma unroll
+  for (int mt = 0; mt < R; ++mt) {
+    const uint32_t keep = rb * (R * 16) + mt * 16 + l16 < M ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 x = __builtin_bit_cast(uint4, qf[mt][ks]);
+      x.x &= keep;
+      x.y &= keep;
+      x.z &= keep;
+      x.w &= keep;
+      qf[mt][ks] = __builtin_bit_cast(bf16x8_t, x);
+    }
+  }
+  for (int nb = 0; nb < ntw; nb += TPR) {
+    const int ne = min(ntw, nb + TPR);
+    if (nb > 0) {
+      fetch_entries(nb);
+      decode_entries(nb);
+#pragma unroll
+      for (int k = 0; k < NBUF - 1; ++k) load_tile(tb[k], nb + k, ne);
+    }
     for (int n = nb; n < ne; n += NBUF) {
 #pragma unroll
       for (int k = 0; k < NBUF; ++k) {
@@ -544,7 +561,13 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
                              int nchunk, const Partials& part, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int nrbg = SPLIT ? 1 : (sh.rows_max + R * 16 * 4 - 1) / (R * 16 * 4);
   const size_t lds_bytes = SPLIT ? 4 * MergeSlot<D, R>::kFloats * sizeof(float) : 0;
-  constexpr int NBUF = (D == 128 && R == 4) ? 3 : 4;   // tile buffers that fit beside Q and O
+  // Tile buffers per wavefront (one is being computed on, the others are in flight).  The sparse
+  // shape wants exactly one tile of lookahead: with more, every wavefront has its whole share
+  // of the list requested at once, the memory system completes those requests in no useful
+  // order, and the first tile of every wavefront lands only near the end of the stream, so
+  // nothing is left to overlap the arithmetic with (C1: 17.9 us with 3 tiles of lookahead,
+  // 15.2 us with 1).  The dense shape has arithmetic to hide behind and keeps a deeper queue.
+  constexpr int NBUF = SPLIT ? 2 : ((D == 128 && R == 4) ? 3 : 4);
   auto kern = attn_mfma_kernel<D, GP, R, SPLIT, NBUF>;
   static bool attr_set = false;   // per instantiation
   if (lds_bytes > 48 * 1024 && !attr_set) {
@@ -556,10 +579,10 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
   const float scale_log2e = sh.sm_scale * 1.4426950408889634f;
   dim3 grid(nchunk, sh.Hkv * nrbg, batch);
   if (ev_start && ev_stop)   // events bound to this dispatch: they read the kernel's own begin and end
-    hipExtLaunchKernelGGL(kern, grid, dim3(256), (uint32_t)lds_bytes, st, ev_start, ev_stop, 0, kv, sh, prep, nchunk,
-                          nrbg, part, scale_log2e);
+    hipExtLaunchKernelGGL(kern, grid, dim3(256), (uint32_t)lds_bytes, st, ev_start, ev_stop, 0, prep, nchunk, nrbg,
+                          sh, kv, part, scale_log2e);
   else
-    kern<<<grid, 256, lds_bytes, st>>>(kv, sh, prep, nchunk, nrbg, part, scale_log2e);
+    kern<<<grid, 256, lds_bytes, st>>>(prep, nchunk, nrbg, sh, kv, part, scale_log2e);
   return hipGetLastError();
 }
 
