@@ -4,8 +4,8 @@
 //   A        = top-n tokens by delta, {delta > tau}, or the smallest set of top tokens that
 //              carries a fraction tau of the block's total delta
 //
-// The score is a pure streaming read of 2*H elements per token (16-byte loads, wavefront
-// butterfly + one LDS hop).  The ranking is by counting: with B <= 1024 tokens,
+// The score is a pure streaming read of 2*H elements per token (16-byte loads, a wavefront
+// reduction in DPP / lane-swap steps, one LDS hop).  The ranking is by counting: with B <= 1024 tokens,
 // rank_i = #{j : delta_j > delta_i or (delta_j == delta_i and j < i)} is B compares per
 // thread out of LDS, cheaper than any sort and deterministic under ties.
 #include "losa_device.h"
@@ -14,7 +14,8 @@
 namespace losa {
 
 // Both steps in one launch: one workgroup per block token computes its score; the workgroup
-// that draws the last ticket of a sequence ranks the B scores and writes the active set.
+// that draws the last ticket of a sequence ranks the B scores and writes the active set
+// (mode < 0: scores only - the step's scoring kernel then does the ranking itself).
 // Scores travel in agent-scope atomic stores (written through to memory) and the ranking
 // workgroup reads them with plain loads: every score has one writer in this launch, no
 // reader before the ticket, and the caches were invalidated when the launch began.

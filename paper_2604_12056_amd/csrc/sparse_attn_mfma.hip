@@ -18,7 +18,7 @@
 // same token order, which is all a contraction needs.
 //
 // No LDS and no barrier in the main loop: K/V go global -> registers in operand layout,
-// several tiles ahead.  Two work shapes:
+// one tile ahead in the sparse shape and two or three in the dense one.  Two work shapes:
 //   split-pages (rows <= 64): the four wavefronts of a workgroup take interleaved tiles and
 //       combine their (reference, sum, O) through LDS at the end, so one partial leaves
 //       the workgroup;
