@@ -58,7 +58,7 @@ hipError_t launch_page_bounds(hipStream_t st, int dtype, const KvView& kv, const
                               int first_page, int num_pages_in_range);
 
 // ---- score_pages.hip
-constexpr int kMaxSelectPages = 256 * 64;   // pages per sequence the register-resident top-k handles
+constexpr int kMaxSelectPages = 1024 * 16;   // pages per sequence the register-resident top-k handles
 // ranking != NULL (bfloat16, B <= 256, not the cumulative-mass mode): the scoring workgroups derive the
 // active set from `delta` themselves and write mask / active_idx / active_count; the active_idx /
 // active_count arguments are then outputs of this launch, not inputs.

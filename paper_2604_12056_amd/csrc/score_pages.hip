@@ -323,8 +323,8 @@ __device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need
   }
 }
 
-// Per-query top pages by radix select, register resident (thread t owns the E consecutive
-// pages [t*E, t*E+E); P <= 256*E), fused with the union and the hand-over described above.
+// Per-query top pages by radix select, register resident (thread t of NT owns the E consecutive
+// pages [t*E, t*E+E); P <= NT*E: 256 threads x 8 up to 2048 pages, 1024 threads x 8 or 16 beyond), fused with the union and the hand-over described above.
 // The radix runs on keys relative to the row's smallest key and starts at the highest bit of
 // the row's largest one (a block min/max finds both), so the first histogram is already
 // spread over many buckets instead of piling every key onto the few exponent patterns the
@@ -333,15 +333,16 @@ __device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need
 // which replaces the remaining histogram passes.  With more keys per thread a histogram pass
 // costs more, so direct ranking pays for larger buckets.
 template <int E> struct RankMax { static constexpr int value = E >= 32 ? 256 : 64; };
-template <int E>
-__global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
+template <int E, int NT>
+__global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
                                                            const float* __restrict__ scores, int topk, SelectOut out) {
-  constexpr int WORDS = 256 * E / 32;
+  constexpr int WORDS = NT * E / 32;
+  constexpr int NW = NT / 64;   // wavefronts
   __shared__ uint32_t hist[256];
   __shared__ uint32_t rowbits[WORDS];
   constexpr int kRankMax = RankMax<E>::value;
   __shared__ __attribute__((aligned(16))) uint32_t cand[kRankMax];
-  __shared__ uint32_t s_bucket, s_lo[4], s_hi[4], s_kth;
+  __shared__ uint32_t s_bucket, s_lo[NW], s_hi[NW], s_kth;
   __shared__ int s_need, s_last, s_count, s_ncand;
   __shared__ int scan[17];
   const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
@@ -352,20 +353,12 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   // so these loads travel together with the loads of the counts below (entries past the
   // sequence's pages are masked later).  Otherwise they wait until the row is known to exist.
   const float* row = scores + ((size_t)head * sh.rows_max + min(r, sh.rows_max - 1)) * sh.max_pages;
-  // With 8 keys per thread each thread simply loads its own 32 contiguous bytes.  With 32 or 64
-  // keys per thread that pattern (lanes 128 or 256 bytes apart, every cache line revisited by
-  // 8 instructions) thrashes the 32 KiB vector cache, so the row is loaded coalesced instead
-  // (float4 number tid + 256*k) and handed to its owners through LDS afterwards (own_row).
-  constexpr bool STAGED = E >= 32;
-  extern __shared__ __attribute__((aligned(16))) float stage[];   // STAGED: 256 * (E + 4) floats
-  const bool vec_row = (sh.max_pages & 3) == 0 && (STAGED || p_first + E <= sh.max_pages);
   float raw[E];
-  auto load_row = [&]() {
-    if (vec_row) {
+  auto load_row = [&]() {   // thread t: pages [t*E, t*E+E), 32 or 64 contiguous bytes
+    if (p_first + E <= sh.max_pages && (sh.max_pages & 3) == 0) {
 #pragma unroll
       for (int i = 0; i < E; i += 4) {
-        const int v4 = STAGED ? min(tid + 256 * (i / 4), sh.max_pages / 4 - 1) : (p_first + i) / 4;
-        const float4 v = reinterpret_cast<const float4*>(row)[v4];
+        const float4 v = *reinterpret_cast<const float4*>(row + p_first + i);
         raw[i] = v.x;
         raw[i + 1] = v.y;
         raw[i + 2] = v.z;
@@ -374,25 +367,6 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     } else {
 #pragma unroll
       for (int i = 0; i < E; ++i) raw[i] = row[min(p_first + i, sh.max_pages - 1)];
-    }
-  };
-  // STAGED: pages 4*(tid + 256k).. were loaded; afterwards raw[i] is page p_first + i.  A thread's
-  // E keys sit E + 4 floats apart in LDS, which keeps both the writes and the reads conflict free.
-  auto own_row = [&]() {
-    if (!STAGED || !vec_row) return;
-#pragma unroll
-    for (int i = 0; i < E; i += 4) {
-      const int p = 4 * (tid + 256 * (i / 4));   // first page of this float4 (p < 256 * E)
-      *reinterpret_cast<float4*>(stage + (p / E) * (E + 4) + p % E) = make_float4(raw[i], raw[i + 1], raw[i + 2], raw[i + 3]);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < E; i += 4) {
-      const float4 v = *reinterpret_cast<const float4*>(stage + tid * (E + 4) + i);
-      raw[i] = v.x;
-      raw[i + 1] = v.y;
-      raw[i + 2] = v.z;
-      raw[i + 3] = v.w;
     }
   };
   if (out.rows_known) load_row();
@@ -411,27 +385,26 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     const int vpr = sh.d / 8;
     const bf16_t* q = (const bf16_t*)out.q;
     uint4* dst = reinterpret_cast<uint4*>(out.prep.q_act + (size_t)head * sh.rows_max * sh.d);
-    for (int v0 = tid; v0 < M * vpr; v0 += 256 * QV) {
+    for (int v0 = tid; v0 < M * vpr; v0 += NT * QV) {
       int tok[QV];
 #pragma unroll
-      for (int k = 0; k < QV; ++k) tok[k] = out.active_idx[(size_t)b * sh.B + min((v0 + 256 * k) / vpr, M - 1) / sh.G];
+      for (int k = 0; k < QV; ++k) tok[k] = out.active_idx[(size_t)b * sh.B + min((v0 + NT * k) / vpr, M - 1) / sh.G];
       uint4 qv[QV];
 #pragma unroll
       for (int k = 0; k < QV; ++k) {
-        const int rr = min((v0 + 256 * k) / vpr, M - 1), cv = (v0 + 256 * k) % vpr;
+        const int rr = min((v0 + NT * k) / vpr, M - 1), cv = (v0 + NT * k) % vpr;
         const int tc = (unsigned)tok[k] < (unsigned)sh.B ? tok[k] : 0;
         qv[k] = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tc) * sh.Hq + j * sh.G + rr % sh.G) * sh.d)[cv];
       }
 #pragma unroll
       for (int k = 0; k < QV; ++k)
-        if (v0 + 256 * k < M * vpr)
-          dst[v0 + 256 * k] = (unsigned)tok[k] < (unsigned)sh.B ? qv[k] : make_uint4(0u, 0u, 0u, 0u);
+        if (v0 + NT * k < M * vpr)
+          dst[v0 + NT * k] = (unsigned)tok[k] < (unsigned)sh.B ? qv[k] : make_uint4(0u, 0u, 0u, 0u);
     }
     return;
   }
   if (r >= M) return;
   if (!out.rows_known) load_row();
-  own_row();
   const int words = (sh.max_pages + 31) / 32;
   const int a = r / sh.G, h = j * sh.G + r % sh.G;
   int32_t* tk = out.topk_out ? out.topk_out + (((size_t)b * sh.B + a) * sh.Hq + h) * topk : nullptr;
@@ -440,7 +413,7 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   uint32_t key[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) key[i] = i < nmine ? order_key(raw[i]) : 0u;
-  for (int w = tid; w < WORDS; w += 256) rowbits[w] = 0u;
+  for (int w = tid; w < WORDS; w += NT) rowbits[w] = 0u;
 
   const bool all = Kp >= P;
   uint32_t prefix = 0u, pmask = 0u;
@@ -463,8 +436,13 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     }
     if (tid == 0) s_ncand = 0;
     __syncthreads();
-    lo = min(min(s_lo[0], s_lo[1]), min(s_lo[2], s_lo[3]));
-    hi = max(max(s_hi[0], s_hi[1]), max(s_hi[2], s_hi[3]));
+    lo = s_lo[0];
+    hi = s_hi[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+      lo = min(lo, s_lo[w]);
+      hi = max(hi, s_hi[w]);
+    }
     // Keys are taken relative to the row minimum from here on (order is unchanged): the
     // first digit then resolves the row's actual range into 128..256 buckets wherever that
     // range lies, instead of splitting at whatever power of two happens to fall inside it.
@@ -477,7 +455,7 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
       pmask = hb >= 31 ? 0u : ~((2u << hb) - 1u);
       prefix = 0u;
       for (int shift = max(hb - 7, 0);; shift = max(shift - 8, 0)) {
-        hist[tid] = 0u;
+        if (tid < 256) hist[tid] = 0u;
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < E; ++i)
@@ -585,7 +563,7 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     if (bits[0]) atomicOr(&rowbits[p_first / 32], bits[0]);
   }
   if (tk)
-    for (int k = tot_sel + tid; k < topk; k += 256) tk[k] = -1;
+    for (int k = tot_sel + tid; k < topk; k += NT) tk[k] = -1;
   __syncthreads();
   // ---- hand-over: the last row of this (sequence, head) builds the union.
   // The row bitmap travels in agent-scope atomic stores (written through to memory, past the
@@ -593,7 +571,7 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   // ticket".  A full agent-scope fence would also work but writes back and invalidates whole
   // L2 slices, once per workgroup.
   uint32_t* myrow = out.rowmaps + ((size_t)head * sh.rows_max + r) * words;
-  for (int w = tid; w < words; w += 256)
+  for (int w = tid; w < words; w += NT)
     __hip_atomic_store(&myrow[w], w < WORDS ? rowbits[w] : 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __builtin_amdgcn_s_waitcnt(0);
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
@@ -611,11 +589,11 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   int32_t* sel = out.sel_pages + (size_t)head * out.cap;
   int32_t* ent = out.prep.entries ? out.prep.entries + (size_t)head * sh.max_pages : nullptr;
   __shared__ int wordbase[WORDS];
-  for (int w = tid; w < WORDS; w += 256) rowbits[w] = 0u;
+  for (int w = tid; w < WORDS; w += NT) rowbits[w] = 0u;
   int phys[E];
   if (ent) {
 #pragma unroll
-    for (int i = 0; i < E; ++i) phys[i] = kv.page_indices[base + min(tid + 256 * i, max(P - 1, 0))];
+    for (int i = 0; i < E; ++i) phys[i] = kv.page_indices[base + min(tid + NT * i, max(P - 1, 0))];
   }
   __syncthreads();
   const uint32_t* maps = out.rowmaps + (size_t)head * sh.rows_max * words;
@@ -626,9 +604,9 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
     // since each cache line of the row bitmaps has exactly one writer in this launch and no
     // reader before this point, the caches were invalidated when the launch began, and the
     // writer's stores went through to memory (agent scope) before its ticket was drawn.
-    for (int w0 = 0; w0 < wordsP; w0 += 256) {
-      const int nw = min(256, wordsP - w0);
-      const int groups = 256 / nw;
+    for (int w0 = 0; w0 < wordsP; w0 += NT) {
+      const int nw = min(NT, wordsP - w0);
+      const int groups = NT / nw;
       const int ww = w0 + tid % nw, rg = tid / nw;
       if (rg < groups) {
         uint32_t acc = 0u;
@@ -648,7 +626,7 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   }
   __syncthreads();
   int base_out = 0;
-  for (int w0 = 0; w0 < WORDS; w0 += 256) {   // exclusive popcount prefix per word
+  for (int w0 = 0; w0 < WORDS; w0 += NT) {   // exclusive popcount prefix per word
     const int w = w0 + tid;
     const int c = w < wordsP ? __popc(rowbits[w]) : 0;
     int total;
@@ -664,12 +642,12 @@ __global__ __launch_bounds__(256) void select_pages_kernel(KvView kv, Shape sh, 
   int wb[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {   // all LDS reads first: one latency, not one per page
-    wd[i] = rowbits[(tid + 256 * i) >> 5];
-    wb[i] = wordbase[(tid + 256 * i) >> 5];
+    wd[i] = rowbits[(tid + NT * i) >> 5];
+    wb[i] = wordbase[(tid + NT * i) >> 5];
   }
 #pragma unroll
   for (int i = 0; i < E; ++i) {
-    const int page = tid + 256 * i;
+    const int page = tid + NT * i;
     if (page < P && ((wd[i] >> (page & 31)) & 1u)) {
       const int at = wb[i] + __popc(wd[i] & ((1u << (page & 31)) - 1u));
       if (at < out.cap) {
@@ -743,23 +721,17 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
   const int rows = rows_hint >= 1 && rows_hint < sh.rows_max ? rows_hint : sh.rows_max;
   dim3 grid(rows + 1, sh.Hkv, batch);   // + the query-gather workgroup
   const int pages = max_seq_pages < sh.max_pages ? max_seq_pages : sh.max_pages;
-  if (pages <= 256 * 8) {
-    select_pages_kernel<8><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
-  } else if (pages <= 256 * 32) {
-    select_pages_kernel<32><<<grid, 256, 256 * (32 + 4) * sizeof(float), st>>>(kv, sh, active_count, scores, topk, out);
-  } else if (pages <= kMaxSelectPages) {
-    constexpr size_t lds = 256 * (64 + 4) * sizeof(float);   // above the default dynamic limit
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&select_pages_kernel<64>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
-    select_pages_kernel<64><<<grid, 256, lds, st>>>(kv, sh, active_count, scores, topk, out);
-  } else {
+  // Few keys per thread keep the unrolled code small (it has to come through the instruction
+  // cache on every launch) and the loads contiguous: longer sequences get more threads, not
+  // more keys per thread.
+  if (pages <= 256 * 8)
+    select_pages_kernel<8, 256><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
+  else if (pages <= 1024 * 8)
+    select_pages_kernel<8, 1024><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out);
+  else if (pages <= kMaxSelectPages)
+    select_pages_kernel<16, 1024><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out);
+  else
     return hipErrorInvalidValue;
-  }
   return hipGetLastError();
 }
 
