@@ -151,14 +151,38 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
   __shared__ int act_list[kRankTokens];
   __shared__ int rscan[17];
   const bool ranked = ra.delta != nullptr;   // uniform over the launch
+  const bool writes_active = ranked && bx == 0 && j == 0;   // this workgroup publishes the active set
+  if (bx * 64 >= P && !writes_active) {                      // no pages here and nothing to publish
+    if (bx == 0 && tid == 0) aux.reset(b * sh.Hkv + j, 0);   // (P == 0: nothing will be selected either)
+    return;
+  }
+  const bool live = p0 < P;   // a wavefront without pages still helps staging and keeps the barriers
+
+  // Everything that can be fetched before the active set is known is requested first: the
+  // locality scores, then the metadata rows of this wavefront's pages (two dependent round
+  // trips: page table, then the rows), which then travel while the ranking runs.
+  float my_delta = 0.f;
+  if (ranked && tid < sh.B) my_delta = ra.delta[(size_t)b * sh.B + tid];
+  // A operands: metadata rows of page p0 + l16 (a valid page is read for lanes past P, never stored)
+  const int pg = max(0, min(p0 + l16, P - 1));
+  int phys = P > 0 ? kv.page_indices[base + pg] : 0;
+  if ((unsigned)phys >= (unsigned)kv.num_pages) phys = 0;
+  const bf16_t* mrow = (const bf16_t*)kv.meta + ((size_t)phys * sh.Hkv + j) * 2 * D;
+  bf16x8_t amin[KS], amax[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    amin[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(mrow + ks * 32 + qd * 8));
+    amax[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(mrow + D + ks * 32 + qd * 8));
+  }
+
   int M;
   if (ranked) {
     const int B = sh.B;   // <= kRankTokens (checked by the launcher)
-    if (tid < B) sdelta[tid] = ra.delta[(size_t)b * B + tid];
+    if (tid < B) sdelta[tid] = my_delta;
     __syncthreads();
     int act = 0;
     if (tid < B) {
-      const float di = sdelta[tid];
+      const float di = my_delta;
       if (ra.mode == LOSA_SEL_THRESHOLD) {
         act = di > ra.tau;
       } else {
@@ -173,7 +197,7 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
     int n_act;
     const int pos = block_exclusive_scan(act, rscan, &n_act);
     if (act) act_list[pos] = tid;
-    if (bx == 0 && j == 0) {
+    if (writes_active) {
       if (tid < B) ra.mask[(size_t)b * B + tid] = (uint8_t)act;
       if (act) ra.active_idx[(size_t)b * B + pos] = tid;
       for (int i = n_act + tid; i < B; i += 256) ra.active_idx[(size_t)b * B + i] = -1;
@@ -185,21 +209,9 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
     M = min(active_count[b], sh.B) * sh.G;
   }
   if (bx == 0 && tid == 0) aux.reset(b * sh.Hkv + j, M);
-  if (bx * 64 >= P) return;   // whole workgroup
+  if (bx * 64 >= P) return;   // whole workgroup (only the publishing one gets here without pages)
   if (M <= 0) return;
-  const bool live = p0 < P;   // a wavefront without pages still helps staging and keeps the barriers
 
-  // A operands: metadata rows of page p0 + l16 (a valid page is read for lanes past P, never stored)
-  const int pg = min(p0 + l16, P - 1);
-  int phys = kv.page_indices[base + pg];
-  if ((unsigned)phys >= (unsigned)kv.num_pages) phys = 0;
-  const bf16_t* mrow = (const bf16_t*)kv.meta + ((size_t)phys * sh.Hkv + j) * 2 * D;
-  bf16x8_t amin[KS], amax[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    amin[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(mrow + ks * 32 + qd * 8));
-    amax[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(mrow + D + ks * 32 + qd * 8));
-  }
   const bool vec_ok = (sh.max_pages & 3) == 0 && p0 + 16 <= P;
   float* out_base = scores + ((size_t)b * sh.Hkv + j) * sh.rows_max * sh.max_pages;
 
