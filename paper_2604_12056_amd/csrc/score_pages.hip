@@ -351,7 +351,8 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   constexpr int WORDS = NT * E / 32;
   constexpr int NW = NT / 64;   // wavefronts
   __shared__ uint32_t hist[256];
-  __shared__ uint32_t rowbits[WORDS];
+  __shared__ uint32_t rowbits[WORDS];   // this row's picks
+  __shared__ uint32_t ubits[WORDS];     // union of the head's rows (used by the workgroup that builds it)
   constexpr int kRankMax = RankMax<E>::value;
   __shared__ __attribute__((aligned(16))) uint32_t cand[kRankMax];
   __shared__ uint32_t s_bucket, s_lo[NW], s_hi[NW], s_kth;
@@ -425,7 +426,12 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   uint32_t key[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) key[i] = i < nmine ? order_key(raw[i]) : 0u;
-  for (int w = tid; w < WORDS; w += NT) rowbits[w] = 0u;
+  // LDS that must start at zero is cleared now, while the scores are still on their way
+  for (int w = tid; w < WORDS; w += NT) {
+    rowbits[w] = 0u;
+    ubits[w] = 0u;
+  }
+  if (tid < 256) hist[tid] = 0u;
 
   const bool all = Kp >= P;
   uint32_t prefix = 0u, pmask = 0u;
@@ -466,9 +472,13 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
       const int hb = 31 - __clz((int)diff);          // no key has a bit above hb
       pmask = hb >= 31 ? 0u : ~((2u << hb) - 1u);
       prefix = 0u;
+      bool first_pass = true;   // the histogram was cleared at the top (a barrier has passed since)
       for (int shift = max(hb - 7, 0);; shift = max(shift - 8, 0)) {
-        if (tid < 256) hist[tid] = 0u;
-        __syncthreads();
+        if (!first_pass) {
+          if (tid < 256) hist[tid] = 0u;
+          __syncthreads();
+        }
+        first_pass = false;
 #pragma unroll
         for (int i = 0; i < E; ++i)
           if (i < nmine && (key[i] & pmask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1u);
@@ -601,13 +611,11 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   int32_t* sel = out.sel_pages + (size_t)head * out.cap;
   int32_t* ent = out.prep.entries ? out.prep.entries + (size_t)head * sh.max_pages : nullptr;
   __shared__ int wordbase[WORDS];
-  for (int w = tid; w < WORDS; w += NT) rowbits[w] = 0u;
   int phys[E];
   if (ent) {
 #pragma unroll
     for (int i = 0; i < E; ++i) phys[i] = kv.page_indices[base + min(tid + NT * i, max(P - 1, 0))];
   }
-  __syncthreads();
   const uint32_t* maps = out.rowmaps + (size_t)head * sh.rows_max * words;
   {
     // Thread t ORs bitmap word (t mod nw) of every `groups`-th row in registers, 16 independent
@@ -632,7 +640,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
 #pragma unroll
           for (int k = 0; k < 16; ++k) acc |= (r0 + groups * k < M) ? v[k] : 0u;
         }
-        if (acc) atomicOr(&rowbits[ww], acc);
+        if (acc) atomicOr(&ubits[ww], acc);
       }
     }
   }
@@ -640,7 +648,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   int base_out = 0;
   for (int w0 = 0; w0 < WORDS; w0 += NT) {   // exclusive popcount prefix per word
     const int w = w0 + tid;
-    const int c = w < wordsP ? __popc(rowbits[w]) : 0;
+    const int c = w < wordsP ? __popc(ubits[w]) : 0;
     int total;
     const int ex = block_exclusive_scan(c, scan, &total);
     if (w < WORDS) wordbase[w] = base_out + ex;
@@ -654,7 +662,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   int wb[E];
 #pragma unroll
   for (int i = 0; i < E; ++i) {   // all LDS reads first: one latency, not one per page
-    wd[i] = rowbits[(tid + NT * i) >> 5];
+    wd[i] = ubits[(tid + NT * i) >> 5];
     wb[i] = wordbase[(tid + NT * i) >> 5];
   }
 #pragma unroll
