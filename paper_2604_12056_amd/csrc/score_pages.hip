@@ -219,7 +219,7 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
   // each row once instead of once per wavefront.  A row is D bfloat16 plus 16 bytes of padding:
   // the 16 lanes that read the same 16-byte column of 16 consecutive rows then fall on
   // different banks.
-  constexpr int kRows = 128, VPR = D / 8, STRIDE = D * 2 + 16;   // bytes
+  constexpr int kRows = 64, VPR = D / 8, STRIDE = D * 2 + 16;   // bytes; 64 rows cover the usual active sets in one go and keep LDS small enough for 8 workgroups per CU
   __shared__ __attribute__((aligned(16))) unsigned char qs[kRows * STRIDE];
   for (int r0 = 0; r0 < M; r0 += kRows) {
     const int nrows = min(kRows, M - r0);
