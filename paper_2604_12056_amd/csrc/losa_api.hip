@@ -287,8 +287,14 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
                              bool prepared, float* o_p, float* lse_p) {
   const int upper = sel_pages ? (cap < max_seq_pages ? cap : max_seq_pages) : max_seq_pages;
   const bool mfma = ctx->cfg.dtype == LOSA_BF16;
+  if (!active_idx) rows_upper = ctx->sh.rows_max;   // every token is active: the count is known
   const bool hinted = rows_upper >= 1 && rows_upper <= ctx->sh.rows_max;
   if (!hinted) rows_upper = ctx->sh.rows_max;
+  // Row count known only on the device (threshold / cumulative-mass selection): both work shapes
+  // of the matrix-core kernel are launched, each serving the (sequence, head) pairs whose count
+  // falls in its range, so that a small active set still gets the shape built for it.  Needs
+  // the two shapes to agree on the number of chunks, which they do up to 256 rows.
+  const bool both_shapes = mfma && !hinted && ctx->sh.rows_max > 64 && ctx->sh.rows_max <= 256;
   // matrix-core kernel: up to 64 rows ride in one workgroup; more rows -> groups of 4 x 64 rows
   const int row_groups = mfma ? (rows_upper <= 64 ? 1 : (ctx->sh.rows_max + 255) / 256) : (ctx->sh.rows_max + 31) / 32;
   const int nchunk = pick_nchunk(ctx, batch, upper, mfma ? row_groups : 1);
@@ -299,8 +305,13 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
     if (e != hipSuccess) return hip_fail(ctx, "attn_prepare launch", e);
   }
   {
-    StageTimer timer(ctx, st, LOSA_STAGE_ATTN, /*bind_to_dispatch=*/mfma);
-    if (mfma)
+    StageTimer timer(ctx, st, LOSA_STAGE_ATTN, /*bind_to_dispatch=*/mfma && !both_shapes);
+    if (both_shapes) {
+      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, 64, ctx->part, nullptr, nullptr, 0, 64);
+      if (e == hipSuccess)
+        e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, ctx->sh.rows_max, ctx->part, nullptr, nullptr,
+                             64, 0x7fffffff);
+    } else if (mfma)
       e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, rows_upper, ctx->part, timer.start(),
                            timer.stop());
     else

@@ -92,7 +92,7 @@ struct MergeSlot {   // LDS image of one wavefront's state: O as [row tile][chan
 // flows is entries -> pages.
 template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv,
-                                                        Partials part, float scale_log2e) {
+                                                        Partials part, float scale_log2e, int m_lo, int m_hi) {
   constexpr int KS = D / 32;    // k-steps of the score product
   constexpr int NT = D / 16;    // channel tiles of the output
   constexpr int PPT = 32 / GP;  // pages per 32-token tile
@@ -130,7 +130,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnPrepared prep, int n
   const int ntiles = (U + PPT - 1) / PPT;
   // M <= 0: nothing active; chunk >= ntiles: this workgroup owns no tile; third: no rows for this
   // wavefront in the split-rows shape (which uses no barrier)
-  if ((M <= 0) | (chunk >= ntiles) | (!SPLIT_PAGES && rb * (R * 16) >= M)) return;
+  // fourth: this launch only serves row counts in (m_lo, m_hi] (the host may not know the count
+  // and then launches both work shapes, each taking its own range)
+  if ((M <= 0) | (chunk >= ntiles) | (!SPLIT_PAGES && rb * (R * 16) >= M) | (M <= m_lo) | (M > m_hi)) return;
   const int ntw = tfirst < ntiles ? (ntiles - 1 - tfirst) / tstep + 1 : 0;   // this wavefront's tiles
 
   bf16x8_t qf[R][KS];
@@ -558,7 +560,8 @@ hipError_t launch_attn_prepare(hipStream_t st, const KvView& kv, const Shape& sh
 
 template <int D, int GP, int R, bool SPLIT>
 static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
-                             int nchunk, const Partials& part, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                             int nchunk, const Partials& part, hipEvent_t ev_start, hipEvent_t ev_stop, int m_lo,
+                             int m_hi) {
   const int nrbg = SPLIT ? 1 : (sh.rows_max + R * 16 * 4 - 1) / (R * 16 * 4);
   const size_t lds_bytes = SPLIT ? 4 * MergeSlot<D, R>::kFloats * sizeof(float) : 0;
   // Tile buffers per wavefront (one is being computed on, the others are in flight).  The sparse
@@ -580,31 +583,33 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
   dim3 grid(nchunk, sh.Hkv * nrbg, batch);
   if (ev_start && ev_stop)   // events bound to this dispatch: they read the kernel's own begin and end
     hipExtLaunchKernelGGL(kern, grid, dim3(256), (uint32_t)lds_bytes, st, ev_start, ev_stop, 0, prep, nchunk, nrbg,
-                          sh, kv, part, scale_log2e);
+                          sh, kv, part, scale_log2e, m_lo, m_hi);
   else
-    kern<<<grid, 256, lds_bytes, st>>>(prep, nchunk, nrbg, sh, kv, part, scale_log2e);
+    kern<<<grid, 256, lds_bytes, st>>>(prep, nchunk, nrbg, sh, kv, part, scale_log2e, m_lo, m_hi);
   return hipGetLastError();
 }
 
 template <int D, int GP>
 static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
-                            int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1) {
-  if (rows_upper <= 16) return launch_one<D, GP, 1, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
-  if (rows_upper <= 32) return launch_one<D, GP, 2, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
-  if (rows_upper <= 48) return launch_one<D, GP, 3, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
-  if (rows_upper <= 64) return launch_one<D, GP, 4, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
-  return launch_one<D, GP, 4, false>(st, kv, sh, batch, prep, nchunk, part, e0, e1);
+                            int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1, int m_lo,
+                            int m_hi) {
+  if (rows_upper <= 16) return launch_one<D, GP, 1, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
+  if (rows_upper <= 32) return launch_one<D, GP, 2, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
+  if (rows_upper <= 48) return launch_one<D, GP, 3, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
+  if (rows_upper <= 64) return launch_one<D, GP, 4, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
+  return launch_one<D, GP, 4, false>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
 }
 
 hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
-                            int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1) {
+                            int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1, int m_lo,
+                            int m_hi) {
   if (batch <= 0 || nchunk <= 0) return hipSuccess;
   if (sh.d == 128) {
-    if (sh.g == 16) return launch_dg<128, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1);
-    return launch_dg<128, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1);
+    if (sh.g == 16) return launch_dg<128, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi);
+    return launch_dg<128, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi);
   }
-  if (sh.g == 16) return launch_dg<64, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1);
-  return launch_dg<64, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1);
+  if (sh.g == 16) return launch_dg<64, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi);
+  return launch_dg<64, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi);
 }
 
 }  // namespace losa
