@@ -552,8 +552,7 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
   // computes them: its end-of-kernel hand-over (store, wait, ticket, reload, rank) drops out
   // of the step's chain of dependent launches.
   InKernelRanking ranking{ctx->delta, (int)mode, 0, 0.f, mk, ctx->active_idx, ctx->active_count};
-  const bool rank_in_scores = ctx->rank_in_scores && ctx->cfg.dtype == LOSA_BF16 && ctx->sh.B <= 256 &&
-                              mode != LOSA_SEL_MASS;
+  const bool rank_in_scores = ctx->rank_in_scores && ctx->cfg.dtype == LOSA_BF16 && ctx->sh.B <= 256;
   if (rank_in_scores) {
     s = parse_select(ctx, (int)mode, param, &ranking.n, &ranking.tau);
     if (s != LOSA_OK) return s;

@@ -59,7 +59,7 @@ hipError_t launch_page_bounds(hipStream_t st, int dtype, const KvView& kv, const
 
 // ---- score_pages.hip
 constexpr int kMaxSelectPages = 1024 * 16;   // pages per sequence the register-resident top-k handles
-// ranking != NULL (bfloat16, B <= 256, not the cumulative-mass mode): the scoring workgroups derive the
+// ranking != NULL (bfloat16, B <= 256): the scoring workgroups derive the
 // active set from `delta` themselves and write mask / active_idx / active_count; the active_idx /
 // active_count arguments are then outputs of this launch, not inputs.
 struct InKernelRanking {

@@ -43,7 +43,7 @@ struct ScoreAux {
 constexpr int kRankTokens = 256;
 struct RankArgs {
   const float* delta;     // [batch*B] locality scores; NULL: use the active list passed to the kernel
-  int mode, n;            // LOSA_SEL_TOPK / FRACTION (n = count) or LOSA_SEL_THRESHOLD (tau)
+  int mode, n;            // LOSA_SEL_TOPK / FRACTION (n = count), LOSA_SEL_THRESHOLD or LOSA_SEL_MASS (tau)
   float tau;
   uint8_t* mask;          // outputs, written by workgroup (0, 0, b)
   int32_t* active_idx;
@@ -180,20 +180,44 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
     const int B = sh.B;   // <= kRankTokens (checked by the launcher)
     if (tid < B) sdelta[tid] = my_delta;
     __syncthreads();
-    int act = 0;
-    if (tid < B) {
-      const float di = my_delta;
-      if (ra.mode == LOSA_SEL_THRESHOLD) {
-        act = di > ra.tau;
-      } else {
-        int rank = 0;
-        for (int k = 0; k < B; ++k) {
-          const float dk = sdelta[k];
-          rank += (dk > di) || (dk == di && k < tid);
-        }
-        act = rank < ra.n;
+    int act = 0, rank = 0;
+    if (tid < B && ra.mode != LOSA_SEL_THRESHOLD) {
+      for (int k = 0; k < B; ++k) {
+        const float dk = sdelta[k];
+        rank += (dk > my_delta) || (dk == my_delta && k < tid);
       }
     }
+    int n_take = ra.n;
+    if (ra.mode == LOSA_SEL_MASS) {
+      // Cumulative-mass rule, as in the stand-alone kernel: scores in descending order, summed
+      // in that order in float by one thread; A is the shortest prefix reaching tau * total.
+      __shared__ float sorted[kRankTokens];
+      __shared__ int s_take;
+      if (tid < B) sorted[rank] = my_delta;
+      __syncthreads();
+      if (tid == 0) {
+        float total = 0.f;
+        for (int k = 0; k < B; ++k) total += sorted[k];
+        const float target = ra.tau * total;
+        int cnt = 0;
+        if (total > 0.f) {
+          float run = 0.f;
+          cnt = B;
+          for (int k = 0; k < B; ++k) {
+            run += sorted[k];
+            if (run >= target) {
+              cnt = k + 1;
+              break;
+            }
+          }
+          if (!(ra.tau > 0.f)) cnt = 0;
+        }
+        s_take = cnt;
+      }
+      __syncthreads();
+      n_take = s_take;
+    }
+    if (tid < B) act = ra.mode == LOSA_SEL_THRESHOLD ? my_delta > ra.tau : rank < n_take;
     int n_act;
     const int pos = block_exclusive_scan(act, rscan, &n_act);
     if (act) act_list[pos] = tid;
@@ -698,7 +722,7 @@ hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const
   ScoreAux aux{tickets, sel_count, prep ? prep->ucount : nullptr, prep ? prep->mrows : nullptr};
   RankArgs ra{nullptr, 0, 0, 0.f, nullptr, nullptr, nullptr};
   if (ranking) {
-    if (dtype != LOSA_BF16 || sh.B > kRankTokens || ranking->mode == LOSA_SEL_MASS) return hipErrorInvalidValue;
+    if (dtype != LOSA_BF16 || sh.B > kRankTokens) return hipErrorInvalidValue;
     ra = RankArgs{ranking->delta, ranking->mode, ranking->n, ranking->tau, ranking->mask, ranking->active_idx,
                   ranking->active_count};
   }

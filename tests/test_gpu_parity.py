@@ -94,13 +94,15 @@ def test_losa_step_threshold_and_mass_modes(rig):
 @pytest.mark.parametrize("idx", [0, 2])
 def test_losa_step_with_ranking_in_the_locality_kernel(idx, monkeypatch):
     """losa_step normally lets the scoring kernel rank the locality scores; blocks larger than it
-    handles, and the cumulative-mass mode, take the locality kernel's own ranking.  Forced here
-    for ordinary workloads (the switch is read when the context is created)."""
+    handles (and the float mode) take the locality kernel's own ranking.  Forced here for
+    ordinary workloads, in every selection mode (the switch is read when the context is created)."""
     monkeypatch.setenv("LOSA_RANK_IN_SCORES", "0")
     r = Rig(small_workloads()[idx])
     try:
         check_page_bounds(r)
         run_steps_end_to_end(r, range(r.w.T), orc.SEL_TOPK, float(r.w.n_active), r.w.topk_pages)
+        run_steps_end_to_end(r, [1], orc.SEL_THRESHOLD, 0.01, r.w.topk_pages)
+        run_steps_end_to_end(r, [2], orc.SEL_MASS, 0.5, r.w.topk_pages)
         assert r.near_ties <= 2
     finally:
         r.close()
