@@ -359,28 +359,165 @@ __device__ __forceinline__ void find_bucket_wave0(const uint32_t* hist, int need
   }
 }
 
-// Per-query top pages by radix select, register resident (thread t of NT owns the E consecutive
-// pages [t*E, t*E+E); P <= NT*E: 256 threads x 8 up to 2048 pages, 1024 threads x 8 or 16 beyond), fused with the union and the hand-over described above.
-// The radix runs on keys relative to the row's smallest key and starts at the highest bit of
-// the row's largest one (a block min/max finds both), so the first histogram is already
+// A bucket of at most this many keys is ranked directly instead of by further histogram passes.
+template <int E> struct RankMax { static constexpr int value = E >= 32 ? 256 : 64; };
+
+// LDS state of radix_kth.  hist must be all zero when radix_kth is entered (the caller clears it
+// early; the first barrier inside radix_kth orders that clear before its first use).
+template <int E, int NT>
+struct RadixLds {
+  uint32_t hist[256];
+  __attribute__((aligned(16))) uint32_t cand[RankMax<E>::value];
+  uint32_t bucket, lo[NT / 64], hi[NT / 64], kth;
+  int need, count, ncand;
+};
+
+// Radix select.  It runs on keys relative to the row's smallest key and starts at the highest
+// bit of the row's largest one (a block min/max finds both), so the first histogram is already
 // spread over many buckets instead of piling every key onto the few exponent patterns the
 // scores share.  As soon as the bucket that holds the K-th key has at most RankMax<E> keys,
 // those are copied to LDS and ranked against each other directly (one thread per candidate),
-// which replaces the remaining histogram passes.  With more keys per thread a histogram pass
-// costs more, so direct ranking pays for larger buckets.
-template <int E> struct RankMax { static constexpr int value = E >= 32 ? 256 : 64; };
+// which replaces the remaining histogram passes.
+//
+// The K-th largest of the workgroup's keys (thread t holds key[0..nmine)), Kp < number of keys:
+// on return every key > prefix is among the Kp largest, and of the keys == prefix the first
+// `need` in page order are (all of them when ties_cut is false).  On return the keys have been
+// rebased (the row minimum subtracted); prefix is in the same units.  all: Kp covers every key,
+// nothing to find.  Every thread of the workgroup must call it.
+template <int E, int NT>
+__device__ __forceinline__ void radix_kth(uint32_t (&key)[E], int nmine, int Kp, bool all, RadixLds<E, NT>& L,
+                                          uint32_t& prefix, int& need, bool& ties_cut) {
+  const int tid = threadIdx.x;
+  constexpr int NW = NT / 64;
+  uint32_t pmask = 0u;
+  prefix = 0u;
+  need = Kp;
+  ties_cut = true;   // false once it is known that every key equal to the K-th is picked
+  if (!all) {
+    // highest differing bit of the row's keys
+    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+    for (int i = 0; i < E; ++i)
+      if (i < nmine) {
+        lo = min(lo, key[i]);
+        hi = max(hi, key[i]);
+      }
+    lo = wave_min_u32(lo);
+    hi = wave_max_u32(hi);
+    if ((tid & 63) == 0) {
+      L.lo[tid >> 6] = lo;
+      L.hi[tid >> 6] = hi;
+    }
+    if (tid == 0) L.ncand = 0;
+    __syncthreads();
+    lo = L.lo[0];
+    hi = L.hi[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+      lo = min(lo, L.lo[w]);
+      hi = max(hi, L.hi[w]);
+    }
+    // Keys are taken relative to the row minimum from here on (order is unchanged): the
+    // first digit then resolves the row's actual range into 128..256 buckets wherever that
+    // range lies, instead of splitting at whatever power of two happens to fall inside it.
+#pragma unroll
+    for (int i = 0; i < E; ++i) key[i] -= lo;   // entries past the row's pages are never looked at
+    hi -= lo;
+    const uint32_t diff = hi;
+    if (diff != 0u) {
+      const int hb = 31 - __clz((int)diff);          // no key has a bit above hb
+      pmask = hb >= 31 ? 0u : ~((2u << hb) - 1u);
+      prefix = 0u;
+      bool first_pass = true;   // the histogram was cleared at the top (a barrier has passed since)
+      for (int shift = max(hb - 7, 0);; shift = max(shift - 8, 0)) {
+        if (!first_pass) {
+          if (tid < 256) L.hist[tid] = 0u;
+          __syncthreads();
+        }
+        first_pass = false;
+#pragma unroll
+        for (int i = 0; i < E; ++i)
+          if (i < nmine && (key[i] & pmask) == prefix) atomicAdd(&L.hist[(key[i] >> shift) & 255u], 1u);
+        __syncthreads();
+        if (tid < 64) find_bucket_wave0(L.hist, need, &L.bucket, &L.need, &L.count);
+        __syncthreads();
+        // bits of the digit that lie above bit hb (only when hb < 7) are common to all keys
+        const uint32_t dmask = 0xFFu << shift;
+        prefix = (prefix & ~dmask) | (L.bucket << shift);
+        pmask |= dmask;
+        need = L.need;
+        const int count = L.count;
+        if (shift == 0) {
+          ties_cut = count != need;
+          break;
+        }
+        if (count <= RankMax<E>::value) {
+          // the K-th key is the need-th largest of `count` candidates: rank them directly.
+          // Candidates are packed wavefront by wavefront (one LDS atomic each); their order
+          // in the array does not matter to the ranks.
+          int mine_n = 0;
+#pragma unroll
+          for (int i = 0; i < E; ++i) mine_n += i < nmine && (key[i] & pmask) == prefix;
+          const int incl = wave_inclusive_scan(mine_n);
+          int wbase = 0;
+          if ((tid & 63) == 63) wbase = atomicAdd(&L.ncand, incl);
+          wbase = __builtin_amdgcn_readlane(wbase, 63);
+          int at = wbase + incl - mine_n;
+#pragma unroll
+          for (int i = 0; i < E; ++i)
+            if (i < nmine && (key[i] & pmask) == prefix) L.cand[at++] = key[i];
+          // pad to a whole number of 16-candidate steps with keys that rank below everything
+          if (tid < 16 && count + tid < RankMax<E>::value) L.cand[count + tid] = 0u;
+          __syncthreads();
+          if (tid < count) {
+            const uint32_t mine = L.cand[tid];
+            int gt = 0, ge = 0;
+            for (int u = 0; u < count; u += 16) {
+              uint4 c4[4];
+#pragma unroll
+              for (int k = 0; k < 4; ++k) c4[k] = *reinterpret_cast<const uint4*>(&L.cand[u + 4 * k]);
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+                gt += (c4[k].x > mine) + (c4[k].y > mine) + (c4[k].z > mine) + (c4[k].w > mine);
+                ge += (c4[k].x >= mine) + (c4[k].y >= mine) + (c4[k].z >= mine) + (c4[k].w >= mine);
+              }
+            }
+            // the padding keys (0) count as ">= mine" only for a key that is 0 itself
+            if (mine == 0u) ge -= ((count + 15) & ~15) - count;
+            if (gt < need && need <= ge) {   // every thread that holds the K-th value writes the same
+              L.kth = mine;
+              L.need = need - gt;
+              L.count = ge - gt;
+            }
+          }
+          __syncthreads();
+          prefix = L.kth;
+          pmask = 0xFFFFFFFFu;
+          need = L.need;
+          ties_cut = L.count != need;
+          break;
+        }
+      }
+    } else {
+      prefix = 0u;          // every key is the same: ties by page order
+      pmask = 0xFFFFFFFFu;
+    }
+  } else {
+    __syncthreads();
+  }
+}
+
+// Per-query top pages, register resident (thread t of NT owns the E consecutive pages
+// [t*E, t*E+E); P <= NT*E: 256 threads x 8 up to 2048 pages, 1024 threads x 8 or 16 beyond),
+// fused with the union and the hand-over described above.
 template <int E, int NT>
 __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
                                                            const float* __restrict__ scores, int topk, SelectOut out) {
   constexpr int WORDS = NT * E / 32;
-  constexpr int NW = NT / 64;   // wavefronts
-  __shared__ uint32_t hist[256];
+  __shared__ RadixLds<E, NT> rl;
   __shared__ uint32_t rowbits[WORDS];   // this row's picks
   __shared__ uint32_t ubits[WORDS];     // union of the head's rows (used by the workgroup that builds it)
-  constexpr int kRankMax = RankMax<E>::value;
-  __shared__ __attribute__((aligned(16))) uint32_t cand[kRankMax];
-  __shared__ uint32_t s_bucket, s_lo[NW], s_hi[NW], s_kth;
-  __shared__ int s_need, s_last, s_count, s_ncand;
+  __shared__ int s_last;
   __shared__ int scan[17];
   const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
   const int head = b * sh.Hkv + j;
@@ -455,124 +592,13 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     rowbits[w] = 0u;
     ubits[w] = 0u;
   }
-  if (tid < 256) hist[tid] = 0u;
+  if (tid < 256) rl.hist[tid] = 0u;
 
   const bool all = Kp >= P;
-  uint32_t prefix = 0u, pmask = 0u;
-  int need = Kp;
-  bool ties_cut = true;   // false once it is known that every key equal to the K-th is picked
-  if (!all) {
-    // highest differing bit of the row's keys
-    uint32_t lo = 0xFFFFFFFFu, hi = 0u;
-#pragma unroll
-    for (int i = 0; i < E; ++i)
-      if (i < nmine) {
-        lo = min(lo, key[i]);
-        hi = max(hi, key[i]);
-      }
-    lo = wave_min_u32(lo);
-    hi = wave_max_u32(hi);
-    if ((tid & 63) == 0) {
-      s_lo[tid >> 6] = lo;
-      s_hi[tid >> 6] = hi;
-    }
-    if (tid == 0) s_ncand = 0;
-    __syncthreads();
-    lo = s_lo[0];
-    hi = s_hi[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) {
-      lo = min(lo, s_lo[w]);
-      hi = max(hi, s_hi[w]);
-    }
-    // Keys are taken relative to the row minimum from here on (order is unchanged): the
-    // first digit then resolves the row's actual range into 128..256 buckets wherever that
-    // range lies, instead of splitting at whatever power of two happens to fall inside it.
-#pragma unroll
-    for (int i = 0; i < E; ++i) key[i] -= lo;   // entries past the row's pages are never looked at
-    hi -= lo;
-    const uint32_t diff = hi;
-    if (diff != 0u) {
-      const int hb = 31 - __clz((int)diff);          // no key has a bit above hb
-      pmask = hb >= 31 ? 0u : ~((2u << hb) - 1u);
-      prefix = 0u;
-      bool first_pass = true;   // the histogram was cleared at the top (a barrier has passed since)
-      for (int shift = max(hb - 7, 0);; shift = max(shift - 8, 0)) {
-        if (!first_pass) {
-          if (tid < 256) hist[tid] = 0u;
-          __syncthreads();
-        }
-        first_pass = false;
-#pragma unroll
-        for (int i = 0; i < E; ++i)
-          if (i < nmine && (key[i] & pmask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1u);
-        __syncthreads();
-        if (tid < 64) find_bucket_wave0(hist, need, &s_bucket, &s_need, &s_count);
-        __syncthreads();
-        // bits of the digit that lie above bit hb (only when hb < 7) are common to all keys
-        const uint32_t dmask = 0xFFu << shift;
-        prefix = (prefix & ~dmask) | (s_bucket << shift);
-        pmask |= dmask;
-        need = s_need;
-        const int count = s_count;
-        if (shift == 0) {
-          ties_cut = count != need;
-          break;
-        }
-        if (count <= kRankMax) {
-          // the K-th key is the need-th largest of `count` candidates: rank them directly.
-          // Candidates are packed wavefront by wavefront (one LDS atomic each); their order
-          // in the array does not matter to the ranks.
-          int mine_n = 0;
-#pragma unroll
-          for (int i = 0; i < E; ++i) mine_n += i < nmine && (key[i] & pmask) == prefix;
-          const int incl = wave_inclusive_scan(mine_n);
-          int wbase = 0;
-          if ((tid & 63) == 63) wbase = atomicAdd(&s_ncand, incl);
-          wbase = __builtin_amdgcn_readlane(wbase, 63);
-          int at = wbase + incl - mine_n;
-#pragma unroll
-          for (int i = 0; i < E; ++i)
-            if (i < nmine && (key[i] & pmask) == prefix) cand[at++] = key[i];
-          // pad to a whole number of 16-candidate steps with keys that rank below everything
-          if (tid < 16 && count + tid < kRankMax) cand[count + tid] = 0u;
-          __syncthreads();
-          if (tid < count) {
-            const uint32_t mine = cand[tid];
-            int gt = 0, ge = 0;
-            for (int u = 0; u < count; u += 16) {
-              uint4 c4[4];
-#pragma unroll
-              for (int k = 0; k < 4; ++k) c4[k] = *reinterpret_cast<const uint4*>(&cand[u + 4 * k]);
-#pragma unroll
-              for (int k = 0; k < 4; ++k) {
-                gt += (c4[k].x > mine) + (c4[k].y > mine) + (c4[k].z > mine) + (c4[k].w > mine);
-                ge += (c4[k].x >= mine) + (c4[k].y >= mine) + (c4[k].z >= mine) + (c4[k].w >= mine);
-              }
-            }
-            // the padding keys (0) count as ">= mine" only for a key that is 0 itself
-            if (mine == 0u) ge -= ((count + 15) & ~15) - count;
-            if (gt < need && need <= ge) {   // every thread that holds the K-th value writes the same
-              s_kth = mine;
-              s_need = need - gt;
-              s_count = ge - gt;
-            }
-          }
-          __syncthreads();
-          prefix = s_kth;
-          pmask = 0xFFFFFFFFu;
-          need = s_need;
-          ties_cut = s_count != need;
-          break;
-        }
-      }
-    } else {
-      prefix = 0u;          // every key is the same: ties by page order
-      pmask = 0xFFFFFFFFu;
-    }
-  } else {
-    __syncthreads();
-  }
+  uint32_t prefix;
+  int need;
+  bool ties_cut;
+  radix_kth<E, NT>(key, nmine, Kp, all, rl, prefix, need, ties_cut);
   // picks: keys above the K-th, plus the first `need` keys equal to it in page order
   int my_eq = 0, my_gt = 0;
 #pragma unroll
