@@ -123,6 +123,18 @@ def top_pages(score: np.ndarray, K: int) -> np.ndarray:
     return np.sort(order[: min(K, P)]).astype(np.int32)
 
 
+def shared_top_pages(scores: np.ndarray, K: int) -> np.ndarray:
+    """NOT in the paper: the other reading of "a page budget per KV head".  One page set per
+    (sequence, KV head) for all of its active queries: every page is scored by the largest
+    bound any of those queries gives it (scores [M, P], float32 values), and the min(K, P)
+    best pages are kept - exactly min(K, P) pages are then read, where the per-query budget
+    of the paper reads between K and M*K.  Ties to the smaller page, ascending output."""
+    s32 = np.asarray(scores, dtype=np.float64).astype(np.float32)
+    if s32.shape[0] == 0:
+        return np.zeros(0, dtype=np.int32)
+    return top_pages(s32.max(axis=0), K)
+
+
 def union_pages(sets: Sequence[np.ndarray]) -> np.ndarray:
     """I = union of the I_i, ascending."""
     if len(sets) == 0:

@@ -440,3 +440,34 @@ def test_generators_are_seeded_and_shaped():
     assert len(c2.seq_lens) == 16 and min(c2.seq_lens) >= 8192 and max(c2.seq_lens) <= 32768
     assert [synth.config(i).n_active for i in range(4)] == [8, 6, 5, 3]
     assert [synth.config(i).topk_pages for i in range(4)] == [32, 128, 64, 256]
+
+
+# --------------------------------------------------------------------------
+# Shared page budget per KV head (not in the paper; the alternative reading of the budget)
+# --------------------------------------------------------------------------
+def test_shared_budget_reads_exactly_k_pages_and_reduces_to_the_per_query_rule_for_one_query():
+    rng = np.random.default_rng(77)
+    P, M, K = 40, 6, 7
+    s = rng.normal(size=(M, P)).astype(np.float32)
+    got = orc.shared_top_pages(s, K)
+    assert len(got) == K and np.all(np.diff(got) > 0)
+    assert len(orc.shared_top_pages(s, P + 5)) == P                      # budget above the page count
+    assert np.array_equal(orc.shared_top_pages(s[:1], K), orc.top_pages(s[0], K))   # one query: same rule
+    # brute force: a page is kept iff fewer than K pages beat its best score (ties: smaller page wins)
+    best = s.max(axis=0)
+    want = [p for p in range(P)
+            if sum((best[r] > best[p]) or (best[r] == best[p] and r < p) for r in range(P)) < K]
+    assert list(got) == want
+    # no dropped page has a better best-score than a kept one; the overall best page is always kept
+    kept = np.zeros(P, dtype=bool)
+    kept[got] = True
+    assert best[kept].min() >= best[~kept].max()
+    assert int(np.argmax(best)) in set(orc.shared_top_pages(s, 1))
+    # growing the budget only adds pages
+    assert set(orc.shared_top_pages(s, 5)) <= set(orc.shared_top_pages(s, 9))
+
+
+def test_shared_budget_ties_go_to_the_smaller_page():
+    s = np.zeros((3, 10), dtype=np.float32)
+    s[1, 7] = 1.0
+    assert list(orc.shared_top_pages(s, 4)) == [0, 1, 2, 7]
