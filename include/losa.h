@@ -147,6 +147,19 @@ losa_status losa_score_pages(losa_ctx* ctx, void* stream, const losa_kv* kv, con
                              int32_t topk_pages, int32_t* topk_out,
                              int32_t* sel_pages, int32_t* sel_count, int32_t cap);
 
+/* Variant of (ii-b) with ONE page set per (sequence, KV head) shared by all of its active
+ * queries.  Not in the paper: it is the other reading of "a page budget per KV head".  Every
+ * page is scored by the largest bound any active query of the head gives it (the scores are the
+ * ones defined above), and the min(topk_pages, P_b) best pages are kept (ties: smaller page),
+ * so the attention that follows reads exactly that many pages per head, where the per-query
+ * budget reads between topk_pages and |A|*G*topk_pages.  Feed the result to losa_sparse_attn.
+ *   sel_pages  : int32 [batch, Hkv, cap] logical pages, ascending
+ *   sel_count  : int32 [batch, Hkv]   (0 for a sequence without active tokens)
+ *   cap        : >= min(max P_b, topk_pages) */
+losa_status losa_score_pages_shared(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q,
+                                    const int32_t* active_idx, const int32_t* active_count,
+                                    int32_t topk_pages, int32_t* sel_pages, int32_t* sel_count, int32_t cap);
+
 /* (iii) Prefix attention of the active queries over the selected pages (Attention
  * Decomposition With Online Softmax; eq. update_rule).  For each active token i and head h:
  *   s_t = sm_scale * q . k_t over the valid tokens t of the pages of its KV head's list,

@@ -18,7 +18,7 @@ LOSA_SEL_TOPK, LOSA_SEL_FRACTION, LOSA_SEL_THRESHOLD, LOSA_SEL_MASS = 0, 1, 2, 3
 
 EXPORTS = ["losa_workspace_bytes", "losa_create", "losa_destroy", "losa_last_error", "losa_select_active",
            "losa_page_bounds", "losa_score_pages", "losa_sparse_attn", "losa_step", "losa_profile_enable",
-           "losa_profile_read", "losa_calibration_copy", "losa_block_merge"]
+           "losa_profile_read", "losa_calibration_copy", "losa_block_merge", "losa_score_pages_shared"]
 STAGES = ["locality", "score", "topk", "attn", "merge", "bounds", "block"]
 
 
@@ -68,6 +68,8 @@ def load_library() -> C.CDLL:
     lib.losa_page_bounds.argtypes = [vp, vp, C.POINTER(losa_kv), i32, i32]
     lib.losa_score_pages.restype = C.c_int
     lib.losa_score_pages.argtypes = [vp, vp, C.POINTER(losa_kv), p, p, p, i32, p, p, p, i32]
+    lib.losa_score_pages_shared.restype = C.c_int
+    lib.losa_score_pages_shared.argtypes = [vp, vp, C.POINTER(losa_kv), p, p, p, i32, p, p, i32]
     lib.losa_sparse_attn.restype = C.c_int
     lib.losa_sparse_attn.argtypes = [vp, vp, C.POINTER(losa_kv), p, p, p, p, p, i32, p, p]
     lib.losa_step.restype = C.c_int
@@ -184,6 +186,14 @@ def losa_score_pages(ctx: Context, kv: PagedKV, q, active_idx, active_count, top
     _check(ctx, load_library().losa_score_pages(ctx.handle, _stream(stream), C.byref(s), _ptr(q), _ptr(active_idx),
                                                _ptr(active_count), topk_pages, _ptr(topk_out), _ptr(sel_pages),
                                                _ptr(sel_count), cap))
+
+
+def losa_score_pages_shared(ctx: Context, kv: PagedKV, q, active_idx, active_count, topk_pages: int, sel_pages,
+                            sel_count, cap: int, stream=None):
+    s = kv.as_struct()
+    _check(ctx, load_library().losa_score_pages_shared(ctx.handle, _stream(stream), C.byref(s), _ptr(q),
+                                                      _ptr(active_idx), _ptr(active_count), topk_pages,
+                                                      _ptr(sel_pages), _ptr(sel_count), cap))
 
 
 def losa_sparse_attn(ctx: Context, kv: PagedKV, q, active_idx, active_count, sel_pages, sel_count, cap: int, o_p,

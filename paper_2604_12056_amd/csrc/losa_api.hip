@@ -496,6 +496,36 @@ losa_status losa_score_pages(losa_ctx* ctx, void* stream, const losa_kv* kv, con
                           topk_pages, topk_out, sel_pages, sel_count, cap, /*prepare_attn=*/false, /*rows_upper=*/0);
 }
 
+losa_status losa_score_pages_shared(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q,
+                                    const int32_t* active_idx, const int32_t* active_count, int32_t topk_pages,
+                                    int32_t* sel_pages, int32_t* sel_count, int32_t cap) {
+  if (!ctx) return LOSA_ERR_INVALID_ARG;
+  int msp;
+  losa_status s = check_kv(ctx, kv, true, &msp);
+  if (s != LOSA_OK) return s;
+  if (!q || !active_idx || !active_count || !sel_pages || !sel_count)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_score_pages_shared: NULL pointer");
+  if (topk_pages < 1 || topk_pages > ctx->cfg.max_topk_pages)
+    return fail(ctx, LOSA_ERR_INVALID_ARG, "topk_pages %d outside 1..max_topk_pages (%d)", topk_pages,
+                ctx->cfg.max_topk_pages);
+  const int need = topk_pages < msp ? topk_pages : msp;
+  if (cap < need) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap %d is below min(pages, topk_pages) = %d", cap, need);
+  hipStream_t st = as_stream(stream);
+  const KvView view = view_of(kv);
+  hipError_t e;
+  {
+    StageTimer timer(ctx, st, LOSA_STAGE_SCORE);
+    e = launch_page_scores(st, ctx->cfg.dtype, view, ctx->sh, kv->batch, msp, q, active_idx, active_count, ctx->scores,
+                           ctx->tickets, sel_count, nullptr, nullptr);
+  }
+  if (e != hipSuccess) return hip_fail(ctx, "page_scores launch", e);
+  StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
+  e = launch_shared_select(st, view, ctx->sh, kv->batch, msp, active_count, ctx->scores, topk_pages, sel_pages,
+                           sel_count, cap);
+  if (e != hipSuccess) return hip_fail(ctx, "shared_select launch", e);
+  return LOSA_OK;
+}
+
 losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q, const int32_t* active_idx,
                              const int32_t* active_count, const int32_t* sel_pages, const int32_t* sel_count,
                              int32_t cap, void* o_p, float* lse_p) {

@@ -49,6 +49,10 @@ struct AttnPrepared {
 hipError_t launch_locality_select(hipStream_t st, int dtype, const void* h_cur, const void* h_prev, int batch, int B,
                                   int H, int mode, int n, float tau, float* delta, uint8_t* mask, int32_t* active_idx,
                                   int32_t* active_count, int32_t* tickets);
+// One shared page set per (sequence, KV head): top pages of the scores max-reduced over the head's rows.
+hipError_t launch_shared_select(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
+                                const int32_t* active_count, const float* scores, int topk, int32_t* sel_pages,
+                                int32_t* sel_count, int cap);
 // Locality scores only (no ranking): for the step whose scoring kernel ranks them itself.
 hipError_t launch_locality_delta(hipStream_t st, int dtype, const void* h_cur, const void* h_prev, int batch, int B,
                                  int H, float* delta);

@@ -740,6 +740,101 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   }
 }
 
+// One page set per (sequence, KV head) shared by all of its active queries (not in the paper:
+// the other reading of a per-KV-head budget): every page takes the largest bound any active
+// query of the head gives it, and the K best pages are kept, so exactly min(K, P) pages are
+// read.  One workgroup per (sequence, head): the row maxima are taken in registers on the
+// order-preserving keys (the same pages-per-thread layout as select_pages_kernel), the K-th
+// is found by the same radix select, and the list is emitted in ascending page order by a
+// prefix sum over the threads' pick counts - no hand-over between workgroups is needed.
+template <int E, int NT>
+__global__ __launch_bounds__(NT) void shared_select_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
+                                                            const float* __restrict__ scores, int topk,
+                                                            int32_t* __restrict__ sel_pages,
+                                                            int32_t* __restrict__ sel_count, int cap) {
+  __shared__ RadixLds<E, NT> rl;
+  __shared__ int scan[17];
+  const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int head = b * sh.Hkv + j;
+  const int p_first = tid * E;
+  if (tid < 256) rl.hist[tid] = 0u;
+  const int M = min(active_count[b], sh.B) * sh.G;
+  const int P = max(0, min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages));
+  if (M <= 0 || P <= 0) {
+    if (tid == 0) sel_count[head] = 0;
+    return;
+  }
+  const int nmine = max(0, min(E, P - p_first));
+  const bool vec = p_first + E <= sh.max_pages && (sh.max_pages & 3) == 0;
+  const float* rows = scores + (size_t)head * sh.rows_max * sh.max_pages;
+  uint32_t key[E];
+#pragma unroll
+  for (int i = 0; i < E; ++i) key[i] = 0u;
+  constexpr int RB = E >= 16 ? 2 : 4;   // rows in flight (fewer with more keys per thread: 128 registers at 1024 threads)
+  for (int r0 = 0; r0 < M; r0 += RB) {
+    float v[RB][E];
+#pragma unroll
+    for (int rr = 0; rr < RB; ++rr) {
+      const float* row = rows + (size_t)min(r0 + rr, M - 1) * sh.max_pages;   // clamped: the repeat changes no maximum
+      if (vec) {
+#pragma unroll
+        for (int i = 0; i < E; i += 4) {
+          const float4 x = *reinterpret_cast<const float4*>(row + p_first + i);
+          v[rr][i] = x.x;
+          v[rr][i + 1] = x.y;
+          v[rr][i + 2] = x.z;
+          v[rr][i + 3] = x.w;
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < E; ++i) v[rr][i] = row[min(p_first + i, sh.max_pages - 1)];
+      }
+    }
+#pragma unroll
+    for (int rr = 0; rr < RB; ++rr)
+#pragma unroll
+      for (int i = 0; i < E; ++i) key[i] = max(key[i], order_key(v[rr][i]));
+  }
+#pragma unroll
+  for (int i = 0; i < E; ++i)
+    if (i >= nmine) key[i] = 0u;
+
+  const int Kp = min(topk, P);
+  const bool all = Kp >= P;
+  uint32_t prefix;
+  int need;
+  bool ties_cut;
+  radix_kth<E, NT>(key, nmine, Kp, all, rl, prefix, need, ties_cut);
+
+  int my_eq = 0, my_gt = 0;
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const bool in = i < nmine;
+    my_gt += in && (all || key[i] > prefix);
+    my_eq += in && !all && key[i] == prefix;
+  }
+  int tot_eq, eq_rank = 0;
+  if (ties_cut) eq_rank = block_exclusive_scan(my_eq, scan, &tot_eq);
+  const int mine = my_gt + (ties_cut ? max(0, min(my_eq, need - eq_rank)) : my_eq);
+  int total;
+  int pos = block_exclusive_scan(mine, scan, &total);
+  int32_t* sel = sel_pages + (size_t)head * cap;
+#pragma unroll
+  for (int i = 0; i < E; ++i) {
+    const bool in = i < nmine;
+    bool take = in && (all || key[i] > prefix);
+    if (in && !all && key[i] == prefix) {
+      take = !ties_cut || eq_rank < need;
+      ++eq_rank;
+    }
+    if (take) {
+      if (pos < cap) sel[pos] = p_first + i;
+      ++pos;
+    }
+  }
+  if (tid == 0) sel_count[head] = min(total, cap);
+}
+
 hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
                               int max_seq_pages, const void* q, const int32_t* active_idx,
                               const int32_t* active_count, float* scores, int32_t* tickets, int32_t* sel_count,
@@ -800,6 +895,23 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
     select_pages_kernel<8, 1024><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out);
   else if (pages <= kMaxSelectPages)
     select_pages_kernel<16, 1024><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_shared_select(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
+                                const int32_t* active_count, const float* scores, int topk, int32_t* sel_pages,
+                                int32_t* sel_count, int cap) {
+  if (batch <= 0) return hipSuccess;
+  dim3 grid(sh.Hkv, batch);
+  const int pages = max_seq_pages < sh.max_pages ? max_seq_pages : sh.max_pages;
+  if (pages <= 256 * 8)
+    shared_select_kernel<8, 256><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, sel_pages, sel_count, cap);
+  else if (pages <= 1024 * 8)
+    shared_select_kernel<8, 1024><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, sel_pages, sel_count, cap);
+  else if (pages <= kMaxSelectPages)
+    shared_select_kernel<16, 1024><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, sel_pages, sel_count, cap);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

@@ -183,6 +183,37 @@ def check_score_pages(rig: Rig, t: int, active, topk: int):
     return union
 
 
+def check_score_pages_shared(rig: Rig, t: int, active, topk: int):
+    """The shared-budget variant: one page set per (sequence, KV head), against the oracle's
+    shared_top_pages on the same active sets.  Returns the sets the device produced."""
+    w, blk = rig.w, rig.blk
+    upload_active(rig, active)
+    blk.sel_pages.fill_(-7)
+    L.losa_score_pages_shared(rig.ctx, rig.layer.kv, blk.q[t], blk.active_idx, blk.active_count, topk,
+                              blk.sel_pages, blk.sel_count, blk.cap)
+    torch.cuda.synchronize()
+    scores, _, _ = oracle_selection(rig, t, active, topk)
+    sel = blk.sel_pages.cpu().numpy()
+    cnt = blk.sel_count.cpu().numpy()
+    got_sets = {}
+    for b in range(w.batch):
+        P = w.pages_per_seq[b]
+        Keff = min(topk, P) if len(active[b]) else 0
+        for j in range(w.Hkv):
+            assert cnt[b, j] == Keff, f"shared budget b{b} kv{j}: {cnt[b, j]} pages, expected {Keff}"
+            got = sel[b, j, :Keff]
+            got_sets[(b, j)] = got.astype(np.int32)
+            if Keff == 0:
+                continue
+            assert list(got) == sorted(set(got.tolist())) and got.min() >= 0 and got.max() < P
+            rows = np.stack([scores[(b, int(i), h)] for i in active[b] for h in range(j * w.G, (j + 1) * w.G)])
+            want = orc.shared_top_pages(rows, topk)
+            best64 = rows.max(axis=0)
+            rig.near_ties += check_near_tie_sets(set(got.tolist()), set(want.tolist()), best64, Keff,
+                                                 f"shared pages b{b} kv{j}")
+    return got_sets
+
+
 def check_sparse_attn(rig: Rig, t: int, active, union, dense: bool = False):
     """Feeds the oracle's active sets and unions; compares (o_p, lse_p) on active rows and
     requires every other row to be bit-identical to what it was."""

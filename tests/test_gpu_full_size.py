@@ -56,3 +56,21 @@ def test_long_sequences_up_to_the_page_limit(pages, tail):
     w = synth.config(0).replace(seq_lens=(L,), topk_pages=96, T=3, name=f"C0-{pages}-pages")
     assert w.max_pages == pages
     _run(w, range(3))
+
+
+@pytest.mark.parametrize("pages", [3001, 9004])
+def test_shared_budget_on_long_sequences(pages):
+    """The shared page budget per KV head (one workgroup per head) in its 1024-thread forms."""
+    from parity_util import check_score_pages_shared, check_sparse_attn
+    w = synth.config(0).replace(seq_lens=(16 * (pages - 1) + 9,), topk_pages=96, T=2, name=f"C0-{pages}-pages-shared")
+    rig = Rig(w)
+    try:
+        check_page_bounds(rig)
+        check_sparse_attn(rig, 0, None, None, dense=True)
+        delta = orc.locality_score(rig.inp.h[1], rig.inp.h[0])
+        active = [orc.active_set(delta[:w.B], orc.SEL_TOPK, float(w.n_active))]
+        sets = check_score_pages_shared(rig, 1, active, w.topk_pages)
+        check_sparse_attn(rig, 1, active, sets)
+        assert rig.near_ties <= 2
+    finally:
+        rig.close()

@@ -8,7 +8,8 @@ from oracle import losa_oracle as orc
 from paper_2604_12056_amd import binding as L
 from paper_2604_12056_amd import synth
 
-from parity_util import (Rig, check_page_bounds, check_score_pages, check_select_active, check_sparse_attn,
+from parity_util import (Rig, check_page_bounds, check_score_pages, check_score_pages_shared, check_select_active,
+                         check_sparse_attn,
                          compare_state, run_steps_end_to_end, upload_active, upload_union)
 
 pytestmark = pytest.mark.gpu
@@ -60,6 +61,18 @@ def test_score_pages_and_union(rig):
     check_score_pages(rig, 1, active, w.topk_pages)
     check_score_pages(rig, 2, [np.arange(w.B, dtype=np.int32)] * w.batch, max(1, w.topk_pages // 2))   # all tokens
     check_score_pages(rig, 1, active, 1)
+    assert rig.near_ties <= 2
+
+
+def test_shared_budget_pages_then_attention(rig):
+    """One page set per (sequence, KV head) - exactly min(K, P) pages - and the attention over it."""
+    w = rig.w
+    check_page_bounds(rig)
+    check_sparse_attn(rig, 0, None, None, dense=True)
+    delta = orc.locality_score(rig.inp.h[1], rig.inp.h[0])
+    active = [orc.active_set(delta[b * w.B:(b + 1) * w.B], orc.SEL_TOPK, float(w.n_active)) for b in range(w.batch)]
+    sets = check_score_pages_shared(rig, 1, active, w.topk_pages)
+    check_sparse_attn(rig, 1, active, sets)
     assert rig.near_ties <= 2
 
 
