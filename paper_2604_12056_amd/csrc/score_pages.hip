@@ -664,7 +664,8 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   int phys[E];
   if (ent) {
 #pragma unroll
-    for (int i = 0; i < E; ++i) phys[i] = kv.page_indices[base + min(tid + NT * i, max(P - 1, 0))];
+    for (int i = 0; i < E; ++i)   // (an empty sequence has no entry of its own in the page table)
+      phys[i] = P > 0 ? kv.page_indices[base + min(tid + NT * i, P - 1)] : 0;
   }
   const uint32_t* maps = out.rowmaps + (size_t)head * sh.rows_max * words;
   {

@@ -174,7 +174,7 @@ def test_block_merge_gives_the_full_attention_output(rig):
 
 
 # ------------------------------------------------------------------ degenerate shapes
-@pytest.mark.parametrize("seq_lens", [(1,), (15,), (16,), (17, 1, 33)])
+@pytest.mark.parametrize("seq_lens", [(1,), (15,), (16,), (17, 1, 33), (0, 40), (40, 0)])   # 0: empty prefix
 def test_tiny_prefixes(seq_lens):
     w = synth.config(0).replace(batch=len(seq_lens), seq_lens=tuple(seq_lens), topk_pages=2, T=3, n_active=3)
     rig = Rig(w)
