@@ -185,6 +185,34 @@ def test_tiny_prefixes(seq_lens):
         rig.close()
 
 
+@pytest.mark.parametrize("seq_lens", [(17, 1, 33), (0, 40), (40, 0)])
+def test_tiny_prefixes_float_mode(seq_lens):
+    w = synth.config(0, dtype="f32").replace(batch=len(seq_lens), seq_lens=tuple(seq_lens), topk_pages=2, T=3,
+                                             n_active=3, name="C0-f32-tiny")
+    rig = Rig(w)
+    try:
+        check_page_bounds(rig)
+        run_steps_end_to_end(rig, range(w.T), orc.SEL_TOPK, 3.0, 2)
+    finally:
+        rig.close()
+
+
+def test_fewer_sequences_than_the_context_was_sized_for():
+    """A context created for max_batch sequences serves calls with fewer (kv.batch < max_batch)."""
+    from paper_2604_12056_amd.device_inputs import config_of
+    w = synth.config(2).replace(batch=2, seq_lens=(700, 333), topk_pages=8, T=3)
+    rig = Rig(w)
+    try:
+        rig.ctx.close()
+        cfg = config_of(w, max_topk_pages=w.max_pages)
+        cfg.max_batch = 5
+        rig.ctx = L.losa_create(cfg, "cuda:0")
+        check_page_bounds(rig)
+        run_steps_end_to_end(rig, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+    finally:
+        rig.close()
+
+
 def test_empty_active_set_is_a_no_op():
     w = synth.config(0).replace(T=2)
     rig = Rig(w)
