@@ -213,6 +213,23 @@ def test_fewer_sequences_than_the_context_was_sized_for():
         rig.close()
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,d,g,n", [(16, 28, 4, 128, 16, 5),    # the paper's block of 16 with its top-5
+                                             (48, 6, 6, 64, 32, 7),      # no grouping (G = 1), d = 64 with 32-token pages
+                                             (32, 32, 4, 128, 32, 6),    # G = 8
+                                             (64, 8, 4, 64, 16, 9)])     # G = 2
+def test_other_head_and_block_shapes(B, Hq, Hkv, d, g, n):
+    w = synth.config(0).replace(B=B, Hq=Hq, Hkv=Hkv, d=d, g=g, n_active=n, batch=2, seq_lens=(1900, 777),
+                                topk_pages=6, T=3, name=f"shape-B{B}-Hq{Hq}-Hkv{Hkv}-d{d}-g{g}")
+    rig = Rig(w)
+    try:
+        check_page_bounds(rig)
+        run_steps_end_to_end(rig, range(w.T), orc.SEL_TOPK, float(n), w.topk_pages)
+        run_steps_end_to_end(rig, [1], orc.SEL_THRESHOLD, 0.01, w.topk_pages)
+        assert rig.near_ties <= 2
+    finally:
+        rig.close()
+
+
 def test_empty_active_set_is_a_no_op():
     w = synth.config(0).replace(T=2)
     rig = Rig(w)
