@@ -204,6 +204,19 @@ def main():
     bounds_us = timed_graph(all_bounds)
     dense_us = timed_graph(all_dense)
 
+    # in-block attention + final merge with the prefix statistics (once per step per layer in a model;
+    # reported beside the prefix step, not part of `value`)
+    from paper_2604_12056_amd.device_inputs import to_device
+    kb, vb = synth.make_block_kv(w)
+    dkb, dvb = to_device(kb[1], dev), to_device(vb[1], dev)
+    out_full = torch.empty_like(blocks[0].o_p)
+
+    def all_block_merge():
+        for ell in range(NL):
+            L.losa_block_merge(ctx, q[1], dkb, dvb, blocks[ell].o_p, blocks[ell].lse_p, out_full)
+
+    block_merge_us = timed_graph(all_block_merge)
+
     # ---- the timed sparse steps
     sel_counts = torch.zeros((args.steps, w.batch, w.Hkv), dtype=torch.int32, device=dev)
 
@@ -324,6 +337,7 @@ def main():
         "stage_us": {k: (round(v, 3) if v is not None else None) for k, v in stage_us.items()},
         "dense_init_us_per_layer": round(dense_us, 2),
         "dense_init_GBps": round(sum(w.seq_lens) * w.Hkv * w.d * 2 * e / (dense_us * 1e-6) / 1e9, 1),
+        "block_merge_us_per_layer": round(block_merge_us, 2),
         "page_bounds_us_per_layer": round(bounds_us, 2),
         "page_bounds_GBps": round((sum(w.seq_lens) * w.Hkv * w.d * e + meta_bytes) / (bounds_us * 1e-6) / 1e9, 1),
         "roofline": {"kernel": "attn_partials (split-K sparse paged attention)", "bound": "hbm",

@@ -148,11 +148,8 @@ def test_run_twice_is_bitwise_identical(rig):
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
 
 
-def test_block_merge_gives_the_full_attention_output(rig):
-    """In-block attention + final merge on top of the prefix statistics, against the oracle."""
+def _check_block_merge(rig):
     w, blk = rig.w, rig.blk
-    check_page_bounds(rig)
-    run_steps_end_to_end(rig, range(2), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
     kb, vb = synth.make_block_kv(w)
     from paper_2604_12056_amd.device_inputs import to_device
     dkb, dvb = to_device(kb[1], blk.q.device), to_device(vb[1], blk.q.device)
@@ -171,6 +168,14 @@ def test_block_merge_gives_the_full_attention_output(rig):
     L.losa_block_merge(rig.ctx, blk.q[1], dkb, dvb, blk.o_p, blk.lse_p, out)
     torch.cuda.synchronize()
     assert np.abs(out.cpu().numpy() - ob_ref).max() <= t
+
+
+def test_block_merge_gives_the_full_attention_output(rig):
+    """In-block attention + final merge on top of the prefix statistics, against the oracle."""
+    w = rig.w
+    check_page_bounds(rig)
+    run_steps_end_to_end(rig, range(2), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+    _check_block_merge(rig)
 
 
 # ------------------------------------------------------------------ degenerate shapes
@@ -226,6 +231,7 @@ def test_other_head_and_block_shapes(B, Hq, Hkv, d, g, n):
         run_steps_end_to_end(rig, range(w.T), orc.SEL_TOPK, float(n), w.topk_pages)
         run_steps_end_to_end(rig, [1], orc.SEL_THRESHOLD, 0.01, w.topk_pages)
         assert rig.near_ties <= 2
+        _check_block_merge(rig)
     finally:
         rig.close()
 
