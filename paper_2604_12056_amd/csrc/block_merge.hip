@@ -188,6 +188,12 @@ __global__ __launch_bounds__(256) void block_merge_mfma_kernel(Shape sh, const b
       for (int ks = 0; ks < KS; ++ks)
         kf[tl][hh][ks] = __builtin_bit_cast(bm_bf16x8_t, *reinterpret_cast<const uint4*>(kr + ks * 32 + qd * 8));
     }
+  // the prefix statistics this row will be merged with: requested now, used at the very end
+  const size_t orow_early = ((size_t)b * B + row) * sh.Hq + h;
+  const float Lp = lse_p[orow_early];
+  bm_f32x4_t op[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) op[nt] = *reinterpret_cast<const bm_f32x4_t*>(o_p + orow_early * D + nt * 16 + 4 * qd);
   __syncthreads();
   if (r0 >= B) return;
 
@@ -259,7 +265,6 @@ __global__ __launch_bounds__(256) void block_merge_mfma_kernel(Shape sh, const b
   if (i >= B) return;
   const size_t orow = ((size_t)b * B + i) * sh.Hq + h;
   const float Lb = (m + log2f(l)) * 0.6931471805599453f;
-  const float Lp = lse_p[orow];
   const float Lm = fmaxf(Lb, Lp);
   const float wb = expf(Lb - Lm), wp = expf(Lp - Lm);   // Lp = -inf (empty prefix) gives wp = 0
   const float inv = 1.0f / (wb + wp), inv_l = 1.0f / l;
@@ -267,9 +272,9 @@ __global__ __launch_bounds__(256) void block_merge_mfma_kernel(Shape sh, const b
   for (int nt = 0; nt < NT; ++nt) {
     const size_t at = orow * D + nt * 16 + 4 * qd;
     bm_f32x4_t ob = o[nt] * inv_l;
-    bm_f32x4_t op = {0.f, 0.f, 0.f, 0.f};
-    if (wp > 0.f) op = *reinterpret_cast<const bm_f32x4_t*>(o_p + at);
-    *reinterpret_cast<bm_f32x4_t*>(out + at) = (ob * wb + op * wp) * inv;
+    const bm_f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
+    const bm_f32x4_t opv = wp > 0.f ? op[nt] : zero;   // an empty prefix may hold anything in o_p, NaN included
+    *reinterpret_cast<bm_f32x4_t*>(out + at) = (ob * wb + opv * wp) * inv;
     if (o_b) *reinterpret_cast<bm_f32x4_t*>(o_b + at) = ob;
   }
   if (lse_b && qd == 0) lse_b[orow] = Lb;
