@@ -101,3 +101,13 @@ def test_workspace_size_is_sane():
                               page_size=16, block_size=32, max_pages_per_seq=2048, max_topk_pages=128)
     n = binding.losa_workspace_bytes(cfg)
     assert 1 << 20 < n < 1 << 30
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asking for more must end with a message, not a silent run."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=60)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
