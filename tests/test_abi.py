@@ -85,6 +85,9 @@ def test_workspace_checks_and_argument_validation(lib):
         assert lib.losa_score_pages(ctx, None, C.byref(kv), fake, fake, fake, 17, None, fake, fake, 64) == inv  # K > max
         assert lib.losa_score_pages(ctx, None, C.byref(kv), fake, fake, fake, 4, None, fake, fake, 8) == inv    # cap small
         assert b"worst case" in lib.losa_last_error(ctx)
+        assert lib.losa_score_pages_shared(ctx, None, C.byref(kv), fake, fake, fake, 17, fake, fake, 64) == inv  # K > max
+        assert lib.losa_score_pages_shared(ctx, None, C.byref(kv), fake, fake, fake, 4, fake, fake, 3) == inv    # cap small
+        assert lib.losa_score_pages_shared(ctx, None, C.byref(kv), fake, None, fake, 4, fake, fake, 64) == inv   # NULL list
         assert lib.losa_sparse_attn(ctx, None, C.byref(kv), fake, fake, None, None, None, 0, fake, fake) == inv  # half a pair
         assert lib.losa_sparse_attn(ctx, None, C.byref(kv), fake, None, None, fake, None, 0, fake, fake) == inv
         assert lib.losa_sparse_attn(ctx, None, C.byref(kv), None, None, None, None, None, 0, fake, fake) == inv
