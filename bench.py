@@ -340,7 +340,7 @@ def main():
         "block_merge_us_per_layer": round(block_merge_us, 2),
         "page_bounds_us_per_layer": round(bounds_us, 2),
         "page_bounds_GBps": round((sum(w.seq_lens) * w.Hkv * w.d * e + meta_bytes) / (bounds_us * 1e-6) / 1e9, 1),
-        "roofline": {"kernel": "attn_partials (split-K sparse paged attention)", "bound": "hbm",
+        "roofline": {"kernel": "attn_mfma_kernel (split-K sparse paged attention)" if w.dtype == "bf16" else "attn_partials_generic_kernel", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "frac_of_measured_copy": round(achieved / copy_gbps, 4) if copy_gbps else None,
