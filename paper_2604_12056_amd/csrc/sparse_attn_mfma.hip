@@ -29,6 +29,7 @@
 #include <hip/hip_ext.h>
 #include <math.h>
 
+#include <cstdlib>
 #include <type_traits>
 
 #include "losa_device.h"
@@ -90,8 +91,8 @@ struct MergeSlot {   // LDS image of one wavefront's state: O as [row tile][chan
 // so that a wavefront can issue its page-entry loads, its query loads and the two counts all
 // at once when it starts: the only dependent memory round trip left before key/value data
 // flows is entries -> pages.
-template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv,
+template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF, int NWAVE = 4, bool LDS_TILES = false>
+__global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv,
                                                         Partials part, float scale_log2e, int m_lo, int m_hi) {
   constexpr int KS = D / 32;    // k-steps of the score product
   constexpr int NT = D / 16;    // channel tiles of the output
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnPrepared prep, int n
   const int l16 = lane & 15, qd = lane >> 4;
   const int chunk = blockIdx.x, b = blockIdx.z;
   const int j = SPLIT_PAGES ? blockIdx.y : blockIdx.y / nrbg;
-  const int rb = SPLIT_PAGES ? 0 : (blockIdx.y % nrbg) * 4 + wave;
+  const int rb = SPLIT_PAGES ? 0 : (blockIdx.y % nrbg) * NWAVE + wave;
   const int head = b * sh.Hkv + j;
 
   // Tiles are dealt round-robin: workgroup `chunk` owns tiles chunk, chunk+nchunk, ... of the
@@ -132,7 +133,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnPrepared prep, int n
   // wavefront in the split-rows shape (which uses no barrier)
   // fourth: this launch only serves row counts in (m_lo, m_hi] (the host may not know the count
   // and then launches both work shapes, each taking its own range)
-  if ((M <= 0) | (chunk >= ntiles) | (!SPLIT_PAGES && rb * (R * 16) >= M) | (M <= m_lo) | (M > m_hi)) return;
+  const bool has_rows = SPLIT_PAGES || rb * (R * 16) < M;
+  if ((M <= 0) | (chunk >= ntiles) | (!LDS_TILES && !has_rows) | (M <= m_lo) | (M > m_hi)) return;
   const int ntw = tfirst < ntiles ? (ntiles - 1 - tfirst) / tstep + 1 : 0;   // this wavefront's tiles
 
   bf16x8_t qf[R][KS];
@@ -349,7 +351,136 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnPrepared prep, int n
   // lookahead, not by occupancy.  Every load is issued unconditionally (see load_tile) so that
   // the number of loads in flight at each use is a compile-time constant: a load behind a
   // branch would force a full drain at the join.
+  if constexpr (LDS_TILES) {
+    // ---- shared-tile variant (many rows, 8 wavefronts of R*16 rows, 2 per SIMD): every
+    // wavefront of the workgroup walks the same tiles, so a tile is fetched from memory once per
+    // workgroup (not once per wavefront), put into LDS and read from there by all.  Measured on
+    // the dense initialisation this is 9-14% faster than 4 independent wavefronts of 64 rows.
+    // What it does not buy is overlap of matrix and vector work: counters show matrix-core busy
+    // plus vector-ALU busy adding up to the run time with one or two wavefronts per SIMD, also
+    // when the two of a SIMD are made to alternate their matrix and vector pieces with barriers
+    // (tried: same time), so the many-row shape is bound by the sum of the two, not by memory.
+    //
+    // LDS image of a tile: the matrix-core operands themselves, one 1 KiB block per operand
+    // (2*KS key blocks: half h, k-step ks; then NT value blocks), lane L's 16 bytes at L*16.
+    // Writes and reads are then both lane-linear, hence free of bank conflicts whichever way
+    // the hardware groups lanes; the permutation lives in the global addresses, where it only
+    // costs some coalescing.  Each wavefront fetches BPW of the blocks.  Two LDS buffers: tile
+    // n+1 is written while tile n is computed on; one barrier per tile.
+    constexpr int NBLK = 2 * KS + NT;          // operand blocks per tile
+    constexpr int BPW = NBLK / NWAVE;          // blocks fetched by each wavefront
+    constexpr int BUF = NBLK * 1024;           // bytes of one tile image
+    static_assert(NBLK % NWAVE == 0 && (BPW == 1 || BPW == 2), "operand blocks do not split evenly over the wavefronts");
+    unsigned char* lbase = reinterpret_cast<unsigned char*>(lds);
+    // PD tiles are in flight per workgroup: one register set each (this lane's 16-byte pieces
+    // of its blocks and, in scalar registers, the tile's valid-token counts).  Tile n sits in set
+    // n % PD; all indices below are compile-time constants once the loops are unrolled.
+    constexpr int PD = 2;
+    static_assert(PD <= TPR, "the first PD tiles come from the first batch of page entries");
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));   // a plain vector value: stays in registers
+    struct Stage {
+      u32x4_t v[BPW];
+      int nv[2];
+    };
+    Stage g[PD];
+    // Byte offset of this lane's piece of block i (of this wavefront) inside its page, and which
+    // of the tile's pages it is in (0 or 1): fixed for the whole kernel.
+    int piece_off[BPW];
+    bool piece_second[BPW], piece_is_k[BPW];
+#pragma unroll
+    for (int i = 0; i < BPW; ++i) {
+      const int blk = wave + NWAVE * i;
+      piece_is_k[i] = blk < 2 * KS;
+      if (piece_is_k[i]) {
+        const int h = blk / KS, ks = blk % KS;
+        const int r = 8 * (l16 >> 2) + 4 * h + (l16 & 3);   // token row tt(h, l16) of the tile
+        piece_second[i] = GP == 16 && r >= 16;
+        piece_off[i] = (r % GP) * (D * 2) + ks * 64 + qd * 16;
+      } else {
+        const int ch = (blk - 2 * KS) * 16 + l16;           // value channel
+        piece_second[i] = GP == 16 && qd >= 2;
+        piece_off[i] = ch * (GP * 2) + (GP == 16 ? (qd & 1) : qd) * 16;
+      }
+    }
+    // tile n of this workgroup -> registers.  n >= ntw asks for a tile that does not exist: the
+    // loads are issued all the same (no load behind a branch, so the number in flight at every
+    // wait is a compile-time constant) but read the first page of the pool.
+    auto gload = [&](Stage& st, int n) {
+      const bool real = n < ntw;
+      const int slot = (n * PPT) & 63;
+      const int pa = real ? __builtin_amdgcn_readlane(pg_phys, slot) : 0;
+      const int pb = real ? __builtin_amdgcn_readlane(pg_phys, slot + PPT - 1) : 0;
+      st.nv[0] = real ? __builtin_amdgcn_readlane(pg_valid, slot) : 0;
+      st.nv[1] = real ? __builtin_amdgcn_readlane(pg_valid, slot + PPT - 1) : 0;
+#pragma unroll
+      for (int i = 0; i < BPW; ++i) {
+        const size_t tile = (size_t)(piece_second[i] ? pb : pa) * sh.Hkv + j;
+        const unsigned char* src = reinterpret_cast<const unsigned char*>(piece_is_k[i] ? kv.k_pages : kv.v_pages) +
+                                   tile * (size_t)(GP * D * 2) + piece_off[i];
+        st.v[i] = *reinterpret_cast<const u32x4_t*>(src);
+      }
+    };
+    auto lstore = [&](const Stage& st, int buf) {
+#pragma unroll
+      for (int i = 0; i < BPW; ++i)
+        *reinterpret_cast<u32x4_t*>(lbase + buf * BUF + (wave + NWAVE * i) * 1024 + lane * 16) = st.v[i];
+    };
+    auto lread = [&](Tile& t, int buf) {
+      const unsigned char* tb_ = lbase + buf * BUF + lane * 16;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        t.k[0][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(tb_ + ks * 1024));
+        t.k[1][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(tb_ + (KS + ks) * 1024));
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) t.v[nt] = *reinterpret_cast<const uint4*>(tb_ + (2 * KS + nt) * 1024);
+    };
+    // rows past M hold whatever the workspace held: make them zero queries
+#pragma unroll
+    for (int mt = 0; mt < R; ++mt) {
+      const uint32_t keep = rb * (R * 16) + mt * 16 + l16 < M ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        uint4 x = __builtin_bit_cast(uint4, qf[mt][ks]);
+        x.x &= keep;
+        x.y &= keep;
+        x.z &= keep;
+        x.w &= keep;
+        qf[mt][ks] = __builtin_bit_cast(bf16x8_t, x);
+      }
+    }
+    decode_entries(0);
+#pragma unroll
+    for (int k = 0; k < PD; ++k) gload(g[k], k);
+    lstore(g[0], 0);   // waits for tile 0 only
+    __syncthreads();
+    Tile t;
+    // Iteration n: request tile n + PD into the set tile n has just left, compute on tile n from
+    // LDS buffer n & 1, move tile n + 1 (requested PD - 1 iterations ago) from its registers into
+    // the other buffer, barrier.  The loop runs in groups of PD iterations so that set indices
+    // are constants; iterations past the last tile of a group only keep the barriers in step.
+    for (int n0 = 0; n0 < ntw; n0 += PD) {
+#pragma unroll
+      for (int k = 0; k < PD; ++k) {
+        const int n = n0 + k;
+        t.nv[0] = g[k].nv[0];
+        t.nv[1] = g[k].nv[1];
+        // page entries come in batches of TPR tiles, requested one iteration before they are decoded
+        if ((n + PD) % TPR == 0 && n + PD < ntw) decode_entries(n + PD);
+        if ((n + PD + 1) % TPR == 0) fetch_entries(n + PD + 1);
+        gload(g[k], n + PD);
+        if (has_rows && n < ntw) {
+          lread(t, n & 1);
+          compute_tile(t);
+        }
+        lstore(g[(k + 1) % PD], (n + 1) & 1);
+        __syncthreads();
+      }
+    }
+    if (!has_rows) return;
+  }
   Tile tb[NBUF];
+  if constexpr (!LDS_TILES) {
   decode_entries(0);
 #pragma unroll
   for (int k = 0; k < NBUF - 1; ++k) load_tile(tb[k], k, min(ntw, TPR));
@@ -384,6 +515,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnPrepared prep, int n
       }
     }
   }
+  }   // !LDS_TILES
 
   // each lane summed its own tokens; rows are spread over the 4 lane groups
 #pragma unroll
@@ -558,20 +690,28 @@ hipError_t launch_attn_prepare(hipStream_t st, const KvView& kv, const Shape& sh
   return hipGetLastError();
 }
 
-template <int D, int GP, int R, bool SPLIT>
+// Bytes of LDS the shared-tile variant needs: two images of a 32-token tile (keys and values).
+template <int D, int GP>
+constexpr size_t shared_tile_lds_bytes() {
+  return 2 * (2 * 32 * D * 2);
+}
+
+template <int D, int GP, int R, bool SPLIT, int NWAVE = 4, bool LDS_TILES = false>
 static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                              int nchunk, const Partials& part, hipEvent_t ev_start, hipEvent_t ev_stop, int m_lo,
                              int m_hi) {
-  const int nrbg = SPLIT ? 1 : (sh.rows_max + R * 16 * 4 - 1) / (R * 16 * 4);
-  const size_t lds_bytes = SPLIT ? 4 * MergeSlot<D, R>::kFloats * sizeof(float) : 0;
+  static_assert(!(SPLIT && LDS_TILES) && (SPLIT ? NWAVE == 4 : true), "the split-pages combine is written for 4 wavefronts");
+  const int nrbg = SPLIT ? 1 : (sh.rows_max + R * 16 * NWAVE - 1) / (R * 16 * NWAVE);
+  const size_t lds_bytes = SPLIT ? 4 * MergeSlot<D, R>::kFloats * sizeof(float)
+                                 : (LDS_TILES ? shared_tile_lds_bytes<D, GP>() : 0);
   // Tile buffers per wavefront (one is being computed on, the others are in flight).  The sparse
   // shape wants exactly one tile of lookahead: with more, every wavefront has its whole share
   // of the list requested at once, the memory system completes those requests in no useful
   // order, and the first tile of every wavefront lands only near the end of the stream, so
   // nothing is left to overlap the arithmetic with (C1: 17.9 us with 3 tiles of lookahead,
   // 15.2 us with 1).  The dense shape has arithmetic to hide behind and keeps a deeper queue.
-  constexpr int NBUF = SPLIT ? 2 : ((D == 128 && R == 4) ? 3 : 4);
-  auto kern = attn_mfma_kernel<D, GP, R, SPLIT, NBUF>;
+  constexpr int NBUF = (SPLIT || LDS_TILES) ? 2 : ((D == 128 && R == 4) ? 3 : 4);
+  auto kern = attn_mfma_kernel<D, GP, R, SPLIT, NBUF, NWAVE, LDS_TILES>;
   static bool attr_set = false;   // per instantiation
   if (lds_bytes > 48 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -582,11 +722,21 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
   const float scale_log2e = sh.sm_scale * 1.4426950408889634f;
   dim3 grid(nchunk, sh.Hkv * nrbg, batch);
   if (ev_start && ev_stop)   // events bound to this dispatch: they read the kernel's own begin and end
-    hipExtLaunchKernelGGL(kern, grid, dim3(256), (uint32_t)lds_bytes, st, ev_start, ev_stop, 0, prep, nchunk, nrbg,
-                          sh, kv, part, scale_log2e, m_lo, m_hi);
+    hipExtLaunchKernelGGL(kern, grid, dim3(64 * NWAVE), (uint32_t)lds_bytes, st, ev_start, ev_stop, 0, prep, nchunk,
+                          nrbg, sh, kv, part, scale_log2e, m_lo, m_hi);
   else
-    kern<<<grid, 256, lds_bytes, st>>>(prep, nchunk, nrbg, sh, kv, part, scale_log2e, m_lo, m_hi);
+    kern<<<grid, 64 * NWAVE, lds_bytes, st>>>(prep, nchunk, nrbg, sh, kv, part, scale_log2e, m_lo, m_hi);
   return hipGetLastError();
+}
+
+// Many rows: 8 wavefronts of 32 rows sharing tiles through LDS (LOSA_ATTN_SHARED_TILES=0 falls
+// back to 4 independent wavefronts of 64 rows).
+static bool shared_tiles_enabled() {
+  static const bool on = [] {
+    const char* e = getenv("LOSA_ATTN_SHARED_TILES");
+    return !(e && e[0] == '0');
+  }();
+  return on;
 }
 
 template <int D, int GP>
@@ -597,6 +747,8 @@ static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, i
   if (rows_upper <= 32) return launch_one<D, GP, 2, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   if (rows_upper <= 48) return launch_one<D, GP, 3, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   if (rows_upper <= 64) return launch_one<D, GP, 4, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
+  if (shared_tiles_enabled())
+    return launch_one<D, GP, 2, false, 8, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   return launch_one<D, GP, 4, false>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
 }
 

@@ -221,7 +221,9 @@ def test_fewer_sequences_than_the_context_was_sized_for():
 @pytest.mark.parametrize("B,Hq,Hkv,d,g,n", [(16, 28, 4, 128, 16, 5),    # the paper's block of 16 with its top-5
                                              (48, 6, 6, 64, 32, 7),      # no grouping (G = 1), d = 64 with 32-token pages
                                              (32, 32, 4, 128, 32, 6),    # G = 8
-                                             (64, 8, 4, 64, 16, 9)])     # G = 2
+                                             (64, 8, 4, 64, 16, 9),      # G = 2
+                                             (64, 32, 4, 128, 16, 40),   # 512 query rows per KV head: two row groups of 8 wavefronts
+                                             (64, 28, 4, 64, 32, 64)])   # 448 rows, ragged second row group, every token active
 def test_other_head_and_block_shapes(B, Hq, Hkv, d, g, n):
     w = synth.config(0).replace(B=B, Hq=Hq, Hkv=Hkv, d=d, g=g, n_active=n, batch=2, seq_lens=(1900, 777),
                                 topk_pages=6, T=3, name=f"shape-B{B}-Hq{Hq}-Hkv{Hkv}-d{d}-g{g}")
