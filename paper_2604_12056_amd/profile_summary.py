@@ -68,7 +68,8 @@ def traffic(fetch_dir: str, write_dir: str, copy_bytes: int) -> None:
         fb, wb = fetch[k] * 1024.0 * f_scale, write.get(k, 0.0) * 1024.0 * w_scale
         print(f"# {k[:68]:68s} {n[k]:8d} {fb:14.0f} {wb:14.0f}")
     for k in sorted(fetch):
-        if "attn_mfma_kernel" in k and "true" in k:       # the sparse-step attention kernel
+        # the sparse-step attention kernel is the split-pages shape: fourth template argument true
+        if re.search(r"attn_mfma_kernel<\d+, \d+, \d+, true\b", k):
             print(f"attn_fetch_bytes_per_launch: {fetch[k] * 1024.0 * f_scale:.0f}")
             print(f"attn_write_bytes_per_launch: {write.get(k, 0.0) * 1024.0 * w_scale:.0f}")
             break
