@@ -47,6 +47,7 @@ struct losa_ctx {
   Partials part;
   long part_items;
   long target_workgroups;   // attention workgroups aimed at per launch
+  long score_round;         // scoring workgroups the machine takes in one round (env LOSA_SCORE_ROUND)
   bool rank_in_scores;      // losa_step lets the scoring kernel rank the locality scores (env LOSA_RANK_IN_SCORES=0: off)
   AttnPrepared prep;
   char err[256];
@@ -271,7 +272,7 @@ losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   {
     StageTimer timer(ctx, st, LOSA_STAGE_SCORE);
     e = launch_page_scores(st, ctx->cfg.dtype, kv, ctx->sh, batch, max_seq_pages, q, active_idx, active_count,
-                           ctx->scores, ctx->tickets, sel_count, prep, ranking);
+                           ctx->scores, ctx->tickets, sel_count, prep, ranking, ctx->score_round);
   }
   if (e != hipSuccess) return hip_fail(ctx, "page_scores launch", e);
   StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
@@ -376,6 +377,11 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   ctx->part_items = L.part_items;
   ctx->target_workgroups = kTargetWorkgroups;
   ctx->rank_in_scores = true;
+  ctx->score_round = 5L * 256;   // about five scoring workgroups per CU are resident at once
+  if (const char* env = getenv("LOSA_SCORE_ROUND")) {
+    const long v = atol(env);
+    if (v >= 1) ctx->score_round = v;
+  }
   if (const char* env = getenv("LOSA_RANK_IN_SCORES")) ctx->rank_in_scores = atoi(env) != 0;
   if (const char* env = getenv("LOSA_ATTN_WORKGROUPS")) {   // tuning knob: one workgroup per CU by default
     const long v = atol(env);
@@ -516,7 +522,7 @@ losa_status losa_score_pages_shared(losa_ctx* ctx, void* stream, const losa_kv* 
   {
     StageTimer timer(ctx, st, LOSA_STAGE_SCORE);
     e = launch_page_scores(st, ctx->cfg.dtype, view, ctx->sh, kv->batch, msp, q, active_idx, active_count, ctx->scores,
-                           ctx->tickets, sel_count, nullptr, nullptr);
+                           ctx->tickets, sel_count, nullptr, nullptr, ctx->score_round);
   }
   if (e != hipSuccess) return hip_fail(ctx, "page_scores launch", e);
   StageTimer timer(ctx, st, LOSA_STAGE_TOPK);

@@ -77,7 +77,7 @@ struct InKernelRanking {
 hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
                               const void* q, const int32_t* active_idx, const int32_t* active_count,
                               float* scores, int32_t* tickets, int32_t* sel_count, const AttnPrepared* prep,
-                              const InKernelRanking* ranking);
+                              const InKernelRanking* ranking, long workgroups_per_round);
 hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh, int batch, int max_seq_pages,
                                const void* q, const int32_t* active_idx, const int32_t* active_count,
                                const float* scores, int topk, int32_t* topk_out, int32_t* sel_pages,

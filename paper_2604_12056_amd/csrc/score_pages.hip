@@ -41,6 +41,7 @@ struct ScoreAux {
 // mask / list / count out for the kernels that follow.  This replaces the hand-over at the end
 // of the locality kernel (store, wait, ticket, reload, rank) by B compares per thread here.
 constexpr int kRankTokens = 256;
+constexpr int kMaxTilesPerWg = 4;   // 64-page tiles one scoring workgroup may take
 struct RankArgs {
   const float* delta;     // [batch*B] locality scores; NULL: use the active list passed to the kernel
   int mode, n;            // LOSA_SEL_TOPK / FRACTION (n = count), LOSA_SEL_THRESHOLD or LOSA_SEL_MASS (tau)
@@ -135,56 +136,74 @@ __global__ __launch_bounds__(256) void page_scores_kernel(KvView kv, Shape sh, c
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
-template <int D>
+template <int D, int MAXT>
 __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape sh, const bf16_t* __restrict__ q,
                                                                const int32_t* __restrict__ active_idx,
                                                                const int32_t* __restrict__ active_count,
-                                                               float* __restrict__ scores, ScoreAux aux, RankArgs ra) {
-  const int bx = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
+                                                               float* __restrict__ scores, ScoreAux aux, RankArgs ra,
+                                                               int tpw) {
+  // A workgroup scores tpw (<= MAXT, a template argument so that the one-tile form carries no
+  // code for more) consecutive 64-page tiles: what it does before
+  // the first product (ranking, query staging) is then paid once for all of them, and a
+  // batch of many sequences still fits the machine in one round of workgroups.
+  const int bx = blockIdx.x * tpw, j = blockIdx.y, b = blockIdx.z;
   constexpr int KS = D / 32;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, qd = lane >> 4;
   const int base = kv.page_indptr[b];
   const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
   const int p0 = bx * 64 + wave * 16;
-  __shared__ float sdelta[kRankTokens];
+  __shared__ __attribute__((aligned(16))) float sdelta[kRankTokens];
   __shared__ int act_list[kRankTokens];
   __shared__ int rscan[17];
   const bool ranked = ra.delta != nullptr;   // uniform over the launch
   const bool writes_active = ranked && bx == 0 && j == 0;   // this workgroup publishes the active set
+  auto tile_phys = [&](int t) {   // page whose metadata rows lane l16 feeds for tile t of this workgroup (clamped: always valid)
+    const int pg = max(0, min((bx + t) * 64 + wave * 16 + l16, P - 1));
+    int ph = P > 0 ? kv.page_indices[base + pg] : 0;
+    return (unsigned)ph < (unsigned)kv.num_pages ? ph : 0;
+  };
   if (bx * 64 >= P && !writes_active) {                      // no pages here and nothing to publish
     if (bx == 0 && tid == 0) aux.reset(b * sh.Hkv + j, 0);   // (P == 0: nothing will be selected either)
     return;
   }
-  const bool live = p0 < P;   // a wavefront without pages still helps staging and keeps the barriers
 
   // Everything that can be fetched before the active set is known is requested first: the
   // locality scores, then the metadata rows of this wavefront's pages (two dependent round
   // trips: page table, then the rows), which then travel while the ranking runs.
   float my_delta = 0.f;
   if (ranked && tid < sh.B) my_delta = ra.delta[(size_t)b * sh.B + tid];
-  // A operands: metadata rows of page p0 + l16 (a valid page is read for lanes past P, never stored)
-  const int pg = max(0, min(p0 + l16, P - 1));
-  int phys = P > 0 ? kv.page_indices[base + pg] : 0;
-  if ((unsigned)phys >= (unsigned)kv.num_pages) phys = 0;
-  const bf16_t* mrow = (const bf16_t*)kv.meta + ((size_t)phys * sh.Hkv + j) * 2 * D;
-  bf16x8_t amin[KS], amax[KS];
+  // A operands: metadata rows of page p0 + l16 (a valid page is read for lanes past P, never stored).
+  // The page ids of all of this workgroup's tiles are fetched at once.
+  int physv[MAXT];
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    amin[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(mrow + ks * 32 + qd * 8));
-    amax[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(mrow + D + ks * 32 + qd * 8));
-  }
+  for (int t = 0; t < MAXT; ++t) physv[t] = t < tpw ? tile_phys(t) : 0;
+  bf16x8_t amin[KS], amax[KS];
+  auto load_meta = [&](int phys, bf16x8_t (&mn)[KS], bf16x8_t (&mx)[KS]) {
+    const bf16_t* mrow = (const bf16_t*)kv.meta + ((size_t)phys * sh.Hkv + j) * 2 * D;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      mn[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(mrow + ks * 32 + qd * 8));
+      mx[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(mrow + D + ks * 32 + qd * 8));
+    }
+  };
+  load_meta(physv[0], amin, amax);
 
   int M;
   if (ranked) {
     const int B = sh.B;   // <= kRankTokens (checked by the launcher)
-    if (tid < B) sdelta[tid] = my_delta;
+    sdelta[tid] = tid < B ? my_delta : -INFINITY;   // 256 threads, kRankTokens entries: the padding never outranks a token
     __syncthreads();
     int act = 0, rank = 0;
     if (tid < B && ra.mode != LOSA_SEL_THRESHOLD) {
-      for (int k = 0; k < B; ++k) {
-        const float dk = sdelta[k];
-        rank += (dk > my_delta) || (dk == my_delta && k < tid);
+      // four scores per LDS read, reads independent of one another (a scalar loop pays one LDS
+      // latency per token)
+#pragma unroll 4
+      for (int k = 0; k < B; k += 4) {
+        const f32x4_t dk = *reinterpret_cast<const f32x4_t*>(&sdelta[k]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)   // bitwise on purpose: the short-circuit forms compile to a branch per element
+          rank += (int)(dk[e] > my_delta) | ((int)(dk[e] == my_delta) & (int)(k + e < tid));
       }
     }
     int n_take = ra.n;
@@ -236,7 +255,6 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
   if (bx * 64 >= P) return;   // whole workgroup (only the publishing one gets here without pages)
   if (M <= 0) return;
 
-  const bool vec_ok = (sh.max_pages & 3) == 0 && p0 + 16 <= P;
   float* out_base = scores + ((size_t)b * sh.Hkv + j) * sh.rows_max * sh.max_pages;
 
   // Query rows go through LDS, kRows at a time, so that the four wavefronts (64 pages) fetch
@@ -244,64 +262,87 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
   // the 16 lanes that read the same 16-byte column of 16 consecutive rows then fall on
   // different banks.
   constexpr int kRows = 64, VPR = D / 8, STRIDE = D * 2 + 16;   // bytes; 64 rows cover the usual active sets in one go and keep LDS small enough for 8 workgroups per CU
-  __shared__ __attribute__((aligned(16))) unsigned char qs[kRows * STRIDE];
-  for (int r0 = 0; r0 < M; r0 += kRows) {
-    const int nrows = min(kRows, M - r0);
-    if (r0 > 0) __syncthreads();   // everyone is done reading the previous chunk
-    {
-      // staging: thread -> (row, 16-byte vector); token ids first, then all the row loads
-      constexpr int PER = kRows * VPR / 256;
-      int tok[PER];
+  // Staged already split by sign (score = q+ . max + q- . min): the split is done once per
+  // workgroup by the staging threads, not once per wavefront, tile and row tile.
+  __shared__ __attribute__((aligned(16))) unsigned char qs[2][kRows * STRIDE];   // [0]: q+, [1]: q-
+  bool staged = false;   // LDS holds rows [0, kRows) of this head's active queries
 #pragma unroll
-      for (int k = 0; k < PER; ++k) {
-        const int rr = min((tid + 256 * k) / VPR, nrows - 1);
-        tok[k] = ranked ? act_list[(r0 + rr) / sh.G] : active_idx[(size_t)b * sh.B + (r0 + rr) / sh.G];
+  for (int t = 0; t < MAXT; ++t) {
+    if (t >= tpw || (bx + t) * 64 >= P) break;   // uniform over the workgroup
+    const int p0t = p0 + t * 64;
+    const bool live = p0t < P;   // a wavefront without pages still helps staging and keeps the barriers
+    const bool vec_ok = (sh.max_pages & 3) == 0 && p0t + 16 <= P;
+    // the next tile's metadata rows travel while this tile is scored
+    bf16x8_t nmin[KS], nmax[KS];
+    if (t + 1 < MAXT && t + 1 < tpw) load_meta(physv[t + 1 < MAXT ? t + 1 : t], nmin, nmax);
+    for (int r0 = 0; r0 < M; r0 += kRows) {
+      const int nrows = min(kRows, M - r0);
+      if (!(staged && M <= kRows)) {   // with a single chunk of rows the first tile's staging serves all tiles
+        if (staged) __syncthreads();   // everyone is done reading the previous chunk
+        // staging: thread -> (row, 16-byte vector); token ids first, then all the row loads
+        constexpr int PER = kRows * VPR / 256;
+        int tok[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+          const int rr = min((tid + 256 * k) / VPR, nrows - 1);
+          tok[k] = ranked ? act_list[(r0 + rr) / sh.G] : active_idx[(size_t)b * sh.B + (r0 + rr) / sh.G];
+        }
+        uint4 v[PER];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+          const int rr = min((tid + 256 * k) / VPR, nrows - 1), cv = (tid + 256 * k) % VPR;
+          const int tc = (unsigned)tok[k] < (unsigned)sh.B ? tok[k] : 0;
+          v[k] = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tc) * sh.Hq + j * sh.G + (r0 + rr) % sh.G) * D)[cv];
+        }
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+          const int rr = (tid + 256 * k) / VPR, cv = (tid + 256 * k) % VPR;
+          if (rr < nrows) {
+            // per 16-bit half: all-ones where the sign bit is set
+            typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+            const uint32_t keep = (unsigned)tok[k] < (unsigned)sh.B ? 0xFFFFFFFFu : 0u;
+            const u32x4_t x = u32x4_t{v[k].x, v[k].y, v[k].z, v[k].w} & keep;
+            const u32x4_t mk = ((x >> 15) & 0x00010001u) * 0xFFFFu;
+            *reinterpret_cast<u32x4_t*>(qs[0] + rr * STRIDE + cv * 16) = x & ~mk;
+            *reinterpret_cast<u32x4_t*>(qs[1] + rr * STRIDE + cv * 16) = x & mk;
+          }
+        }
+        __syncthreads();
+        staged = true;
       }
-      uint4 v[PER];
+      if (!live) continue;
+      for (int t0 = 0; t0 < nrows; t0 += 16) {
+        const int rr = t0 + l16;           // row of this lane inside the chunk (may be past nrows: masked below)
+        uint4 qpos[KS], qneg[KS];
 #pragma unroll
-      for (int k = 0; k < PER; ++k) {
-        const int rr = min((tid + 256 * k) / VPR, nrows - 1), cv = (tid + 256 * k) % VPR;
-        const int tc = (unsigned)tok[k] < (unsigned)sh.B ? tok[k] : 0;
-        v[k] = reinterpret_cast<const uint4*>(q + (((size_t)b * sh.B + tc) * sh.Hq + j * sh.G + (r0 + rr) % sh.G) * D)[cv];
-      }
+        for (int ks = 0; ks < KS; ++ks) {
+          qpos[ks] = *reinterpret_cast<const uint4*>(qs[0] + min(rr, nrows - 1) * STRIDE + ks * 64 + qd * 16);
+          qneg[ks] = *reinterpret_cast<const uint4*>(qs[1] + min(rr, nrows - 1) * STRIDE + ks * 64 + qd * 16);
+        }
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int k = 0; k < PER; ++k) {
-        const int rr = (tid + 256 * k) / VPR, cv = (tid + 256 * k) % VPR;
-        if (rr < nrows)
-          *reinterpret_cast<uint4*>(qs + rr * STRIDE + cv * 16) =
-              (unsigned)tok[k] < (unsigned)sh.B ? v[k] : make_uint4(0u, 0u, 0u, 0u);
+        for (int ks = 0; ks < KS; ++ks) {
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amax[ks], __builtin_bit_cast(bf16x8_t, qpos[ks]), acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amin[ks], __builtin_bit_cast(bf16x8_t, qneg[ks]), acc, 0, 0, 0);
+        }
+        // acc[e] = score of page p0t + 4*qd + e for query row r0 + t0 + l16
+        if (rr < nrows) {
+          float* dst = out_base + (size_t)(r0 + rr) * sh.max_pages + p0t + 4 * qd;
+          if (vec_ok) {
+            *reinterpret_cast<f32x4_t*>(dst) = acc;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (p0t + 4 * qd + e < P) dst[e] = acc[e];
+          }
+        }
       }
     }
-    __syncthreads();
-    if (!live) continue;
-    for (int t0 = 0; t0 < nrows; t0 += 16) {
-      const int rr = t0 + l16;           // row of this lane inside the chunk (may be past nrows: masked below)
-      uint4 raw[KS];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        raw[ks] = *reinterpret_cast<const uint4*>(qs + min(rr, nrows - 1) * STRIDE + ks * 64 + qd * 16);
-      f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    if (t + 1 < MAXT && t + 1 < tpw) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        // per 16-bit half: all-ones where the sign bit is set
-        auto neg_mask = [](uint32_t x) { return ((x >> 15) & 0x00010001u) * 0xFFFFu; };
-        const uint4 x = raw[ks];
-        const uint4 mk = make_uint4(neg_mask(x.x), neg_mask(x.y), neg_mask(x.z), neg_mask(x.w));
-        const uint4 qneg = make_uint4(x.x & mk.x, x.y & mk.y, x.z & mk.z, x.w & mk.w);
-        const uint4 qpos = make_uint4(x.x & ~mk.x, x.y & ~mk.y, x.z & ~mk.z, x.w & ~mk.w);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amax[ks], __builtin_bit_cast(bf16x8_t, qpos), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(amin[ks], __builtin_bit_cast(bf16x8_t, qneg), acc, 0, 0, 0);
-      }
-      // acc[e] = score of page p0 + 4*qd + e for query row r0 + t0 + l16
-      if (rr < nrows) {
-        float* dst = out_base + (size_t)(r0 + rr) * sh.max_pages + p0 + 4 * qd;
-        if (vec_ok) {
-          *reinterpret_cast<f32x4_t*>(dst) = acc;
-        } else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (p0 + 4 * qd + e < P) dst[e] = acc[e];
-        }
+        amin[ks] = nmin[ks];
+        amax[ks] = nmax[ks];
       }
     }
   }
@@ -839,7 +880,7 @@ __global__ __launch_bounds__(NT) void shared_select_kernel(KvView kv, Shape sh, 
 hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const Shape& sh, int batch,
                               int max_seq_pages, const void* q, const int32_t* active_idx,
                               const int32_t* active_count, float* scores, int32_t* tickets, int32_t* sel_count,
-                              const AttnPrepared* prep, const InKernelRanking* ranking) {
+                              const AttnPrepared* prep, const InKernelRanking* ranking, long workgroups_per_round) {
   if (batch <= 0) return hipSuccess;
   ScoreAux aux{tickets, sel_count, prep ? prep->ucount : nullptr, prep ? prep->mrows : nullptr};
   RankArgs ra{nullptr, 0, 0, 0.f, nullptr, nullptr, nullptr};
@@ -851,12 +892,24 @@ hipError_t launch_page_scores(hipStream_t st, int dtype, const KvView& kv, const
   dim3 grid((max_seq_pages + kScorePages - 1) / kScorePages, sh.Hkv, batch);
   if (grid.x == 0) grid.x = 1;
   if (dtype == LOSA_BF16) {
-    dim3 mgrid((max_seq_pages + 63) / 64, sh.Hkv, batch);
-    if (mgrid.x == 0) mgrid.x = 1;
-    if (sh.d == 128)
-      page_scores_mfma_kernel<128><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux, ra);
-    else
-      page_scores_mfma_kernel<64><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux, ra);
+    // One 64-page tile per workgroup while the grid fits the machine in one round; beyond
+    // that, more tiles per workgroup rather than a second round.
+    const long tiles = max((max_seq_pages + 63) / 64, 1);
+    const long round = max(workgroups_per_round, 1L);
+    int tpw = (int)((tiles * sh.Hkv * batch + round - 1) / round);
+    tpw = max(1, min(tpw, kMaxTilesPerWg));
+    dim3 mgrid((unsigned)((tiles + tpw - 1) / tpw), sh.Hkv, batch);
+    if (sh.d == 128) {
+      if (tpw == 1)
+        page_scores_mfma_kernel<128, 1><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux, ra, 1);
+      else
+        page_scores_mfma_kernel<128, kMaxTilesPerWg><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux, ra, tpw);
+    } else {
+      if (tpw == 1)
+        page_scores_mfma_kernel<64, 1><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux, ra, 1);
+      else
+        page_scores_mfma_kernel<64, kMaxTilesPerWg><<<mgrid, 256, 0, st>>>(kv, sh, (const bf16_t*)q, active_idx, active_count, scores, aux, ra, tpw);
+    }
   } else {
     if (sh.d == 128)
       page_scores_kernel<float, 128><<<grid, 256, 0, st>>>(kv, sh, (const float*)q, active_idx, active_count, scores, aux);

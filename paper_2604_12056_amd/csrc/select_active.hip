@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void locality_select_kernel(const T* __restric
       int rank = 0;
       for (int k = 0; k < B; ++k) {
         const float dk = sd[k];
-        rank += (dk > di) || (dk == di && k < i);
+        rank += (int)(dk > di) | ((int)(dk == di) & (int)(k < i));   // bitwise: no branch per element
       }
       sorted[rank] = di;
     }
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void locality_select_kernel(const T* __restric
         int rank = 0;
         for (int k = 0; k < B; ++k) {
           const float dk = sd[k];
-          rank += (dk > di) || (dk == di && k < i);
+          rank += (int)(dk > di) | ((int)(dk == di) & (int)(k < i));   // bitwise: no branch per element
         }
         act = rank < n;
       }

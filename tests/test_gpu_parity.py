@@ -121,6 +121,26 @@ def test_losa_step_with_ranking_in_the_locality_kernel(idx, monkeypatch):
         r.close()
 
 
+@pytest.mark.parametrize("round_size", ["1", "25", "40"])
+def test_scoring_with_several_tiles_per_workgroup(round_size, monkeypatch):
+    """A batch whose scoring grid would not fit the machine in one round gives each scoring
+    workgroup up to four 64-page tiles.  Forced here on small workloads by shrinking what counts
+    as a round (read when the context is created): ragged tile counts, sequences shorter than a
+    workgroup's share, and more than 64 query rows per head (queries re-staged per tile)."""
+    monkeypatch.setenv("LOSA_SCORE_ROUND", round_size)
+    for w in (small_workloads()[2],
+              synth.config(0).replace(B=32, Hq=32, Hkv=4, d=128, g=16, n_active=12, batch=3, seq_lens=(5000, 1031, 40),
+                                      topk_pages=6, T=2, name="several-tiles-96-rows")):
+        r = Rig(w)
+        try:
+            check_page_bounds(r)
+            run_steps_end_to_end(r, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+            run_steps_end_to_end(r, [1], orc.SEL_MASS, 0.5, w.topk_pages)
+            assert r.near_ties <= 2
+        finally:
+            r.close()
+
+
 def test_budget_covering_every_page_equals_dense(rig):
     """All tokens active and K >= P: the sparse path must reproduce dense prefix attention."""
     w, blk = rig.w, rig.blk
