@@ -498,7 +498,7 @@ __device__ __forceinline__ void radix_kth(uint32_t (&key)[E], int nmine, int Kp,
           // in the array does not matter to the ranks.
           int mine_n = 0;
 #pragma unroll
-          for (int i = 0; i < E; ++i) mine_n += i < nmine && (key[i] & pmask) == prefix;
+          for (int i = 0; i < E; ++i) mine_n += (int)(i < nmine) & (int)((key[i] & pmask) == prefix);
           const int incl = wave_inclusive_scan(mine_n);
           int wbase = 0;
           if ((tid & 63) == 63) wbase = atomicAdd(&L.ncand, incl);
@@ -640,13 +640,16 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   int need;
   bool ties_cut;
   radix_kth<E, NT>(key, nmine, Kp, all, rl, prefix, need, ties_cut);
-  // picks: keys above the K-th, plus the first `need` keys equal to it in page order
+  // picks: keys above the K-th, plus the first `need` keys equal to it in page order.
+  // (Bitwise logic on purpose: the short-circuit forms compile to a branch per key.)
   int my_eq = 0, my_gt = 0;
+  if (ties_cut || tk) {   // the counts feed the scans below and nothing else
 #pragma unroll
-  for (int i = 0; i < E; ++i) {
-    const bool in = i < nmine;
-    my_gt += in && (all || key[i] > prefix);
-    my_eq += in && !all && key[i] == prefix;
+    for (int i = 0; i < E; ++i) {
+      const int in = i < nmine;
+      my_gt += in & ((int)all | (int)(key[i] > prefix));
+      my_eq += in & (int)!all & (int)(key[i] == prefix);
+    }
   }
   int tot_eq;
   int eq_rank = 0;   // block-uniform branch: ties_cut derives from LDS values every thread read
@@ -658,16 +661,12 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   for (int w = 0; w < (E + 31) / 32; ++w) bits[w] = 0u;
 #pragma unroll
   for (int i = 0; i < E; ++i) {
-    const bool in = i < nmine;
-    bool sel = in && (all || key[i] > prefix);
-    if (in && !all && key[i] == prefix) {
-      sel = !ties_cut || eq_rank < need;
-      ++eq_rank;
-    }
-    if (sel) {
-      bits[i / 32] |= 1u << ((p_first + i) & 31);
-      if (tk) tk[pos++] = p_first + i;
-    }
+    const int in = i < nmine;
+    const int eq = in & (int)!all & (int)(key[i] == prefix);
+    const int sel = (in & ((int)all | (int)(key[i] > prefix))) | (eq & ((int)!ties_cut | (int)(eq_rank < need)));
+    eq_rank += eq;
+    bits[i / 32] |= (uint32_t)sel << ((p_first + i) & 31);
+    if (tk && sel) tk[pos++] = p_first + i;
   }
   if (E >= 32) {
 #pragma unroll
