@@ -100,7 +100,9 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   constexpr int TPR = 64 / PPT; // tiles covered by one page-entry fetch (one entry per lane)
   extern __shared__ __attribute__((aligned(16))) float lds[];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // the wavefront number is the same for all lanes; saying so keeps what derives from it (tile
+  // numbers, loop bounds, page ids, base addresses) in scalar registers and scalar arithmetic
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l16 = lane & 15, qd = lane >> 4;
   const int chunk = blockIdx.x, b = blockIdx.z;
   const int j = SPLIT_PAGES ? blockIdx.y : blockIdx.y / nrbg;
