@@ -47,6 +47,7 @@ struct losa_ctx {
   Partials part;
   long part_items;
   long target_workgroups;   // attention workgroups aimed at per launch
+  long select_round;        // selection workgroups per round (env LOSA_SELECT_ROUND; 0: from the kernel's occupancy)
   long score_round;         // scoring workgroups the machine takes in one round (env LOSA_SCORE_ROUND)
   bool rank_in_scores;      // losa_step lets the scoring kernel rank the locality scores (env LOSA_RANK_IN_SCORES=0: off)
   AttnPrepared prep;
@@ -277,7 +278,8 @@ losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   if (e != hipSuccess) return hip_fail(ctx, "page_scores launch", e);
   StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
   e = launch_select_pages(st, kv, ctx->sh, batch, max_seq_pages, q, active_idx, active_count, ctx->scores, topk,
-                          topk_out, sel_pages, sel_count, cap, ctx->rowmaps, ctx->tickets, prep, rows_upper);
+                          topk_out, sel_pages, sel_count, cap, ctx->rowmaps, ctx->tickets, prep, rows_upper,
+                          ctx->select_round);
   if (e != hipSuccess) return hip_fail(ctx, "select_pages launch", e);
   return LOSA_OK;
 }
@@ -377,6 +379,11 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   ctx->part_items = L.part_items;
   ctx->target_workgroups = kTargetWorkgroups;
   ctx->rank_in_scores = true;
+  ctx->select_round = 0;
+  if (const char* env = getenv("LOSA_SELECT_ROUND")) {
+    const long v = atol(env);
+    if (v >= 1) ctx->select_round = v;
+  }
   ctx->score_round = 5L * 256;   // about five scoring workgroups per CU are resident at once
   if (const char* env = getenv("LOSA_SCORE_ROUND")) {
     const long v = atol(env);

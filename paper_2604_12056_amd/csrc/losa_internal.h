@@ -82,7 +82,7 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
                                const void* q, const int32_t* active_idx, const int32_t* active_count,
                                const float* scores, int topk, int32_t* topk_out, int32_t* sel_pages,
                                int32_t* sel_count, int cap, uint32_t* rowmaps, int32_t* tickets,
-                               const AttnPrepared* prep, int rows_hint);
+                               const AttnPrepared* prep, int rows_hint, long workgroups_per_round);
 
 // ---- sparse_attn.hip (element-generic kernel, merge) and sparse_attn_mfma.hip (bfloat16 matrix-core kernel)
 // Both deal the 32-token tiles of a (sequence, KV head) page list round-robin to `nchunk` work items.

@@ -551,47 +551,53 @@ __device__ __forceinline__ void radix_kth(uint32_t (&key)[E], int nmine, int Kp,
 // Per-query top pages, register resident (thread t of NT owns the E consecutive pages
 // [t*E, t*E+E); P <= NT*E: 256 threads x 8 up to 2048 pages, 1024 threads x 8 or 16 beyond),
 // fused with the union and the hand-over described above.
-template <int E, int NT>
+template <int E, int NT, bool MULTI>
 __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
-                                                           const float* __restrict__ scores, int topk, SelectOut out) {
+                                                           const float* __restrict__ scores, int topk, SelectOut out,
+                                                           int rpw) {
+  // A workgroup selects for rpw consecutive query rows, one after the other (the next row's
+  // scores travel while the current row is selected).  rpw is 1 unless the grid would not fit
+  // the machine in one round: a second round of workgroups costs more than a second row.
+  // MULTI = false is the one-row form (rpw == 1) without the loop's register cost.
   constexpr int WORDS = NT * E / 32;
   __shared__ RadixLds<E, NT> rl;
   __shared__ uint32_t rowbits[WORDS];   // this row's picks
   __shared__ uint32_t ubits[WORDS];     // union of the head's rows (used by the workgroup that builds it)
   __shared__ int s_last;
   __shared__ int scan[17];
-  const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  const int r_first = blockIdx.x * rpw, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
   const int head = b * sh.Hkv + j;
-  const int p_first = tid * E;
+  const int p_first_all = tid * E;
+  const int p_first = p_first_all;
   // When the host knows the row count (every workgroup of the grid has a row), the row's
   // scores are fetched before anything else: the address depends on kernel arguments only,
   // so these loads travel together with the loads of the counts below (entries past the
   // sequence's pages are masked later).  Otherwise they wait until the row is known to exist.
-  const float* row = scores + ((size_t)head * sh.rows_max + min(r, sh.rows_max - 1)) * sh.max_pages;
   float raw[E];
-  auto load_row = [&]() {   // thread t: pages [t*E, t*E+E), 32 or 64 contiguous bytes
+  auto load_row = [&](float (&dst)[E], int r) {   // thread t: pages [t*E, t*E+E), 32 or 64 contiguous bytes
+    const float* row = scores + ((size_t)head * sh.rows_max + min(r, sh.rows_max - 1)) * sh.max_pages;
     if (p_first + E <= sh.max_pages && (sh.max_pages & 3) == 0) {
 #pragma unroll
       for (int i = 0; i < E; i += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(row + p_first + i);
-        raw[i] = v.x;
-        raw[i + 1] = v.y;
-        raw[i + 2] = v.z;
-        raw[i + 3] = v.w;
+        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(row + p_first + i);
+        dst[i] = v[0];
+        dst[i + 1] = v[1];
+        dst[i + 2] = v[2];
+        dst[i + 3] = v[3];
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < E; ++i) raw[i] = row[min(p_first + i, sh.max_pages - 1)];
+      for (int i = 0; i < E; ++i) dst[i] = row[min(p_first + i, sh.max_pages - 1)];
     }
   };
-  if (out.rows_known) load_row();
+  if (out.rows_known) load_row(raw, r_first);
   const int n_act = min(active_count[b], sh.B);
   const int M = n_act * sh.G;
   const int base = kv.page_indptr[b];
   const int P = max(0, min(kv.page_indptr[b + 1] - base, sh.max_pages));
   const int L = kv.seq_lens[b];
 
-  if (r == (int)gridDim.x - 1) {
+  if (blockIdx.x == gridDim.x - 1) {
     // The extra workgroup of every (sequence, head) gathers the head's active query rows into
     // the dense buffer the attention kernel reads, off the path of the selection.  Indices are
     // clamped so that every load can be issued before the one it depends on has been checked.
@@ -618,77 +624,98 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     }
     return;
   }
-  if (r >= M) return;
-  if (!out.rows_known) load_row();
+  if (r_first >= M) return;
+  if (!out.rows_known) load_row(raw, r_first);
   const int words = (sh.max_pages + 31) / 32;
-  const int a = r / sh.G, h = j * sh.G + r % sh.G;
-  int32_t* tk = out.topk_out ? out.topk_out + (((size_t)b * sh.B + a) * sh.Hq + h) * topk : nullptr;
   const int Kp = min(topk, P);
-  const int nmine = max(0, min(E, P - p_first));   // pages of this thread that exist
-  uint32_t key[E];
-#pragma unroll
-  for (int i = 0; i < E; ++i) key[i] = i < nmine ? order_key(raw[i]) : 0u;
+  const int nmine_all = max(0, min(E, P - p_first));   // pages of this thread that exist
   // LDS that must start at zero is cleared now, while the scores are still on their way
   for (int w = tid; w < WORDS; w += NT) {
     rowbits[w] = 0u;
     ubits[w] = 0u;
   }
   if (tid < 256) rl.hist[tid] = 0u;
-
-  const bool all = Kp >= P;
-  uint32_t prefix;
-  int need;
-  bool ties_cut;
-  radix_kth<E, NT>(key, nmine, Kp, all, rl, prefix, need, ties_cut);
-  // picks: keys above the K-th, plus the first `need` keys equal to it in page order.
-  // (Bitwise logic on purpose: the short-circuit forms compile to a branch per key.)
-  int my_eq = 0, my_gt = 0;
-  if (ties_cut || tk) {   // the counts feed the scans below and nothing else
+  const int r_end = MULTI ? min(r_first + rpw, M) : r_first + 1;   // rows [r_first, r_end) are this workgroup's
+#pragma unroll 1
+  for (int r = r_first; r < r_end; ++r) {
+    // Per-thread constants are made opaque once per row: otherwise everything derived from them
+    // (bit masks, predicates, addresses) is computed once ahead of the loop and kept in registers
+    // across it, which costs half the kernel's occupancy.
+    int p_first_r = p_first_all, nmine_r = nmine_all;
+    if constexpr (MULTI) asm volatile("" : "+v"(p_first_r), "+v"(nmine_r));
+    const int p_first = p_first_r, nmine = nmine_r;
+    const int a = r / sh.G, h = j * sh.G + r % sh.G;
+    int32_t* tk = out.topk_out ? out.topk_out + (((size_t)b * sh.B + a) * sh.Hq + h) * topk : nullptr;
+    uint32_t key[E];
 #pragma unroll
+    for (int i = 0; i < E; ++i) key[i] = i < nmine ? order_key(raw[i]) : 0u;
+    if (r + 1 < r_end) load_row(raw, r + 1);   // the next row's scores, on their way during this row's selection
+
+    const bool all = Kp >= P;
+    uint32_t prefix;
+    int need;
+    bool ties_cut;
+    radix_kth<E, NT>(key, nmine, Kp, all, rl, prefix, need, ties_cut);
+    // picks: keys above the K-th, plus the first `need` keys equal to it in page order.
+    // (Bitwise logic on purpose: the short-circuit forms compile to a branch per key.)
+    int my_eq = 0, my_gt = 0;
+    if (ties_cut || tk) {   // the counts feed the scans below and nothing else
+  #pragma unroll
+      for (int i = 0; i < E; ++i) {
+        const int in = i < nmine;
+        my_gt += in & ((int)all | (int)(key[i] > prefix));
+        my_eq += in & (int)!all & (int)(key[i] == prefix);
+      }
+    }
+    int tot_eq;
+    int eq_rank = 0;   // block-uniform branch: ties_cut derives from LDS values every thread read
+    if (ties_cut) eq_rank = block_exclusive_scan(my_eq, scan, &tot_eq);
+    int pos = 0, tot_sel = 0;
+    if (tk) pos = block_exclusive_scan(my_gt + (ties_cut ? max(0, min(my_eq, need - eq_rank)) : my_eq), scan, &tot_sel);
+    uint32_t bits[(E + 31) / 32];
+  #pragma unroll
+    for (int w = 0; w < (E + 31) / 32; ++w) bits[w] = 0u;
+  #pragma unroll
     for (int i = 0; i < E; ++i) {
       const int in = i < nmine;
-      my_gt += in & ((int)all | (int)(key[i] > prefix));
-      my_eq += in & (int)!all & (int)(key[i] == prefix);
+      const int eq = in & (int)!all & (int)(key[i] == prefix);
+      const int sel = (in & ((int)all | (int)(key[i] > prefix))) | (eq & ((int)!ties_cut | (int)(eq_rank < need)));
+      eq_rank += eq;
+      bits[i / 32] |= (uint32_t)sel << ((p_first + i) & 31);
+      if (tk && sel) tk[pos++] = p_first + i;
+    }
+    if (E >= 32) {
+  #pragma unroll
+      for (int w = 0; w < (E + 31) / 32; ++w) rowbits[p_first / 32 + w] = bits[w];   // this thread owns whole words
+    } else {
+      if (bits[0]) atomicOr(&rowbits[p_first / 32], bits[0]);
+    }
+    if (tk)
+      for (int k = tot_sel + tid; k < topk; k += NT) tk[k] = -1;
+    __syncthreads();
+    // ---- hand-over: the last row of this (sequence, head) builds the union.
+    // The row bitmap travels in agent-scope atomic stores (written through to memory, past the
+    // per-die L2 slices); ordering is "my stores have completed (wait count zero), then my
+    // ticket".  A full agent-scope fence would also work but writes back and invalidates whole
+    // L2 slices, once per workgroup.
+    uint32_t* myrow = out.rowmaps + ((size_t)head * sh.rows_max + r) * words;
+    for (int w = tid; w < words; w += NT)
+      __hip_atomic_store(&myrow[w], w < WORDS ? rowbits[w] : 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (r + 1 < r_end) {
+      // the row bitmap has been read out (the stores above take their data at issue): clear the
+      // LDS state of the next row; its first barrier (inside radix_kth) orders these writes
+      __syncthreads();
+      for (int w = tid; w < WORDS; w += NT) rowbits[w] = 0u;
+      if (tid < 256) rl.hist[tid] = 0u;
     }
   }
-  int tot_eq;
-  int eq_rank = 0;   // block-uniform branch: ties_cut derives from LDS values every thread read
-  if (ties_cut) eq_rank = block_exclusive_scan(my_eq, scan, &tot_eq);
-  int pos = 0, tot_sel = 0;
-  if (tk) pos = block_exclusive_scan(my_gt + (ties_cut ? max(0, min(my_eq, need - eq_rank)) : my_eq), scan, &tot_sel);
-  uint32_t bits[(E + 31) / 32];
-#pragma unroll
-  for (int w = 0; w < (E + 31) / 32; ++w) bits[w] = 0u;
-#pragma unroll
-  for (int i = 0; i < E; ++i) {
-    const int in = i < nmine;
-    const int eq = in & (int)!all & (int)(key[i] == prefix);
-    const int sel = (in & ((int)all | (int)(key[i] > prefix))) | (eq & ((int)!ties_cut | (int)(eq_rank < need)));
-    eq_rank += eq;
-    bits[i / 32] |= (uint32_t)sel << ((p_first + i) & 31);
-    if (tk && sel) tk[pos++] = p_first + i;
-  }
-  if (E >= 32) {
-#pragma unroll
-    for (int w = 0; w < (E + 31) / 32; ++w) rowbits[p_first / 32 + w] = bits[w];   // this thread owns whole words
-  } else {
-    if (bits[0]) atomicOr(&rowbits[p_first / 32], bits[0]);
-  }
-  if (tk)
-    for (int k = tot_sel + tid; k < topk; k += NT) tk[k] = -1;
-  __syncthreads();
-  // ---- hand-over: the last row of this (sequence, head) builds the union.
-  // The row bitmap travels in agent-scope atomic stores (written through to memory, past the
-  // per-die L2 slices); ordering is "my stores have completed (wait count zero), then my
-  // ticket".  A full agent-scope fence would also work but writes back and invalidates whole
-  // L2 slices, once per workgroup.
-  uint32_t* myrow = out.rowmaps + ((size_t)head * sh.rows_max + r) * words;
-  for (int w = tid; w < words; w += NT)
-    __hip_atomic_store(&myrow[w], w < WORDS ? rowbits[w] : 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const int rows_done = r_end - r_first;
   __builtin_amdgcn_s_waitcnt(0);
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
   __syncthreads();
-  if (tid == 0) s_last = __hip_atomic_fetch_add(&out.tickets[head], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == M - 1;
+  // the ticket counts rows: the workgroup whose rows complete the head's M builds the union
+  if (tid == 0)
+    s_last = __hip_atomic_fetch_add(&out.tickets[head], rows_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + rows_done == M;
   __syncthreads();
   if (!s_last) return;
   if (tid == 0) out.tickets[head] = 0;
@@ -922,7 +949,7 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
                                const void* q, const int32_t* active_idx, const int32_t* active_count,
                                const float* scores, int topk, int32_t* topk_out, int32_t* sel_pages,
                                int32_t* sel_count, int cap, uint32_t* rowmaps, int32_t* tickets,
-                               const AttnPrepared* prep, int rows_hint) {
+                               const AttnPrepared* prep, int rows_hint, long workgroups_per_round) {
   if (batch <= 0) return hipSuccess;
   SelectOut out;
   out.topk_out = topk_out;
@@ -937,17 +964,35 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
   out.rows_known = rows_hint >= 1;
   // rows_hint: an upper bound on |A| * G the host happens to know (0: none); rows past it get no workgroup
   const int rows = rows_hint >= 1 && rows_hint < sh.rows_max ? rows_hint : sh.rows_max;
-  dim3 grid(rows + 1, sh.Hkv, batch);   // + the query-gather workgroup
   const int pages = max_seq_pages < sh.max_pages ? max_seq_pages : sh.max_pages;
+  // One row per workgroup while the grid fits the machine in one round (seven 256-thread
+  // workgroups per CU for the one-row form, five for the several-row form, by their register
+  // counts; one 1024-thread workgroup); beyond that, up to four rows per workgroup.
+  const bool small = pages <= 256 * 8;
+  const long fit_one = workgroups_per_round > 0 ? workgroups_per_round : (small ? 7L * 256 : 256L);
+  const long fit_many = workgroups_per_round > 0 ? workgroups_per_round : (small ? 5L * 256 : 256L);
+  const long wgs = (long)(rows + 1) * sh.Hkv * batch;
+  int rpw = wgs <= fit_one ? 1 : (int)((wgs + fit_many - 1) / fit_many);
+  rpw = rpw < 1 ? 1 : (rpw > 4 ? 4 : rpw);
+  dim3 grid((rows + rpw - 1) / rpw + 1, sh.Hkv, batch);   // + the query-gather workgroup
   // Few keys per thread keep the unrolled code small (it has to come through the instruction
   // cache on every launch) and the loads contiguous: longer sequences get more threads, not
   // more keys per thread.
   if (pages <= 256 * 8)
-    select_pages_kernel<8, 256><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out);
+    if (rpw == 1)
+      select_pages_kernel<8, 256, false><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out, 1);
+    else
+      select_pages_kernel<8, 256, true><<<grid, 256, 0, st>>>(kv, sh, active_count, scores, topk, out, rpw);
   else if (pages <= 1024 * 8)
-    select_pages_kernel<8, 1024><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out);
+    if (rpw == 1)
+      select_pages_kernel<8, 1024, false><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out, 1);
+    else
+      select_pages_kernel<8, 1024, true><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out, rpw);
   else if (pages <= kMaxSelectPages)
-    select_pages_kernel<16, 1024><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out);
+    if (rpw == 1)
+      select_pages_kernel<16, 1024, false><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out, 1);
+    else
+      select_pages_kernel<16, 1024, true><<<grid, 1024, 0, st>>>(kv, sh, active_count, scores, topk, out, rpw);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

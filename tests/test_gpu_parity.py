@@ -141,6 +141,28 @@ def test_scoring_with_several_tiles_per_workgroup(round_size, monkeypatch):
             r.close()
 
 
+@pytest.mark.parametrize("round_size", ["1", "60", "100"])
+def test_selection_with_several_rows_per_workgroup(round_size, monkeypatch):
+    """A batch whose selection grid would not fit the machine in one round gives each selection
+    workgroup up to four query rows.  Forced here on small workloads by shrinking what counts as a
+    round (read when the context is created): row counts that are not a multiple of the share,
+    every selection mode (the row count is then known only on the device), per-row lists."""
+    monkeypatch.setenv("LOSA_SELECT_ROUND", round_size)
+    for w in (small_workloads()[2], small_workloads()[4]):
+        r = Rig(w)
+        try:
+            check_page_bounds(r)
+            run_steps_end_to_end(r, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+            run_steps_end_to_end(r, [1], orc.SEL_THRESHOLD, 0.01, w.topk_pages)
+            run_steps_end_to_end(r, [2], orc.SEL_MASS, 0.5, w.topk_pages)
+            delta = orc.locality_score(r.inp.h[1], r.inp.h[0])
+            active = [orc.active_set(delta[i * w.B:(i + 1) * w.B], orc.SEL_TOPK, float(w.n_active)) for i in range(w.batch)]
+            check_score_pages(r, 1, active, w.topk_pages)
+            assert r.near_ties <= 2
+        finally:
+            r.close()
+
+
 def test_budget_covering_every_page_equals_dense(rig):
     """All tokens active and K >= P: the sparse path must reproduce dense prefix attention."""
     w, blk = rig.w, rig.blk
