@@ -268,8 +268,13 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         sc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][ks], qf[mt][ks], sc[mt][1], 0, 0, 0);
       }
     }
-    // ---- phase 2: row maxima of all row tiles, one lazy-rescale decision for the wavefront
-    float s[R][8], m_cand[R];
+    // ---- phase 2: one lazy-rescale decision for the wavefront.  Whether some row's maximum
+    // has overtaken its reference by more than kLag is decided from each lane's own maximum
+    // (a row's lanes share m_run, and scaling by a positive factor keeps the order, so "some
+    // lane exceeds" and "the row maximum exceeds" are the same event); the cross-lane maximum
+    // itself is only taken when that happens, which after the first tile is rare.
+    float s[R][8], tm[R];
+    bool any_up = false;
 #pragma unroll
     for (int mt = 0; mt < R; ++mt) {
 #pragma unroll
@@ -282,19 +287,16 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         for (int e = 0; e < 8; ++e)
           if (e >= lane_valid) s[mt][e] = -INFINITY;
       }
-      const float tm = vmax3(vmax3(s[mt][0], s[mt][1], s[mt][2]), vmax3(s[mt][3], s[mt][4], s[mt][5]),
-                            vmax(s[mt][6], s[mt][7]));
-      m_cand[mt] = max_over_lane_groups(tm) * scale_log2e;
+      tm[mt] = vmax3(vmax3(s[mt][0], s[mt][1], s[mt][2]), vmax3(s[mt][3], s[mt][4], s[mt][5]), vmax(s[mt][6], s[mt][7]));
+      any_up |= tm[mt] * scale_log2e > m_run[mt] + kLag;
     }
-    bool any_up = false;
-#pragma unroll
-    for (int mt = 0; mt < R; ++mt) any_up |= m_cand[mt] > m_run[mt] + kLag;
     if (__any(any_up)) {
 #pragma unroll
       for (int mt = 0; mt < R; ++mt) {
-        const bool up = m_cand[mt] > m_run[mt] + kLag;
-        const float alpha = up ? fast_exp2(m_run[mt] - m_cand[mt]) : 1.0f;
-        m_run[mt] = up ? m_cand[mt] : m_run[mt];
+        const float m_cand = max_over_lane_groups(tm[mt]) * scale_log2e;
+        const bool up = m_cand > m_run[mt] + kLag;
+        const float alpha = up ? fast_exp2(m_run[mt] - m_cand) : 1.0f;
+        m_run[mt] = up ? m_cand : m_run[mt];
         l_run[mt] *= alpha;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) o[mt][nt] *= alpha;
