@@ -294,3 +294,41 @@ def test_empty_active_set_is_a_no_op():
         assert int(blk.mask.sum()) == 0 and int(blk.sel_count.sum()) == 0
     finally:
         rig.close()
+
+
+def _random_workload(seed: int):
+    rng = np.random.Generator(np.random.Philox(seed))
+    B = int(rng.choice([16, 32, 48, 64]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 4, 7, 8]))
+    d = int(rng.choice([64, 128]))
+    g = int(rng.choice([16, 32]))
+    batch = int(rng.integers(1, 5))
+    lens = []
+    for _ in range(batch):
+        kind = rng.integers(0, 4)
+        lens.append(int(rng.integers(0, 3 * g) if kind == 0 else rng.integers(1, 4000)))
+    if max(lens) == 0:
+        lens[0] = 17
+    return synth.config(0).replace(B=B, Hq=Hkv * G, Hkv=Hkv, d=d, g=g, batch=batch, seq_lens=tuple(lens),
+                                   n_active=int(rng.integers(1, B + 1)), topk_pages=int(rng.integers(1, 13)), T=3,
+                                   outliers=str(rng.choice(["fixed4x8", "lognormal"])), seed=7000 + seed,
+                                   name=f"random-{seed}")
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_random_shapes_end_to_end(seed):
+    """Seeded random head / block / page / batch shapes and prefix lengths (some shorter than a
+    page or empty), dense initialisation then sparse steps in a randomly chosen selection mode,
+    every output against the oracle."""
+    w = _random_workload(seed)
+    rng = np.random.Generator(np.random.Philox(100 + seed))
+    mode, param = [(orc.SEL_TOPK, float(w.n_active)), (orc.SEL_FRACTION, w.n_active / w.B),
+                   (orc.SEL_THRESHOLD, 0.01), (orc.SEL_MASS, 0.5)][int(rng.integers(0, 4))]
+    r = Rig(w)
+    try:
+        check_page_bounds(r)
+        run_steps_end_to_end(r, range(w.T), mode, param, w.topk_pages)
+        assert r.near_ties <= 4
+    finally:
+        r.close()
