@@ -342,6 +342,13 @@ def main():
         "union_pages_per_kv_head": round(pages_per_launch / (w.batch * w.Hkv), 1),
         "kv_density": round(float(density), 4),
         "stage_us": {k: (round(v, 3) if v is not None else None) for k, v in stage_us.items()},
+        # the same per-kernel figures grouped as the paper's latency breakdown names them (Latency
+        # Analysis): reuse for stable tokens is "rows never written", so cache management has no kernel
+        "paper_breakdown_us": {
+            "locality_pruning": round(stage_us["locality"] or 0.0, 3),
+            "criticality_estimation": round((stage_us["score"] or 0.0) + (stage_us["topk"] or 0.0), 3),
+            "cache_management": 0.0,
+            "attention_computation": round((stage_us["attn"] or 0.0) + (stage_us["merge"] or 0.0), 3)},
         "dense_init_us_per_layer": round(dense_us, 2),
         "dense_init_GBps": round(sum(w.seq_lens) * w.Hkv * w.d * 2 * e / (dense_us * 1e-6) / 1e9, 1),
         "block_merge_us_per_layer": round(block_merge_us, 2),
