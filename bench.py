@@ -351,6 +351,11 @@ def main():
             "attention_computation": round((stage_us["attn"] or 0.0) + (stage_us["merge"] or 0.0), 3)},
         "dense_init_us_per_layer": round(dense_us, 2),
         "dense_init_GBps": round(sum(w.seq_lens) * w.Hkv * w.d * 2 * e / (dense_us * 1e-6) / 1e9, 1),
+        # the dense pass is the one place near the matrix-core roof: 4*M*d flop per prefix token and KV head
+        # (M = B*G query rows), against 2.5 PFLOP/s dense bf16
+        "dense_init_TFLOPs": round(4.0 * w.B * (w.Hq // w.Hkv) * w.d * sum(w.seq_lens) * w.Hkv / (dense_us * 1e-6) / 1e12, 1),
+        "dense_init_frac_of_mfma_peak": round(4.0 * w.B * (w.Hq // w.Hkv) * w.d * sum(w.seq_lens) * w.Hkv
+                                              / (dense_us * 1e-6) / 2.5e15, 4),
         "block_merge_us_per_layer": round(block_merge_us, 2),
         "page_bounds_us_per_layer": round(bounds_us, 2),
         "page_bounds_GBps": round((sum(w.seq_lens) * w.Hkv * w.d * e + meta_bytes) / (bounds_us * 1e-6) / 1e9, 1),
@@ -375,7 +380,14 @@ def main():
         for t in range(1, 1 + n_cpu):
             orc.losa_step(cache, t, inp0.h[t], inp0.h[t - 1], inp0.q[t], mode, param, topk, w.B, w.Hq, o_ref, L_ref)
         cpu_us = (time.perf_counter() - c0) * 1e6 / n_cpu
+        cpu_model = ""
+        try:
+            with open("/proc/cpuinfo") as f:
+                cpu_model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": round(cpu_us, 1), "unit": "us", "cores": int(cores), "kind": "oracle",
+                               "cpu_model": cpu_model, "host_cpus": os.cpu_count(),
                                "sample": f"sparse steps 1..{n_cpu} of layer 0 of {w.name} (numpy float64 oracle)"}
         # the same oracle held to one thread, on fewer steps (reported beside the figure above)
         try:
