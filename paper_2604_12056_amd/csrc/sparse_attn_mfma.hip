@@ -45,26 +45,15 @@ constexpr float kNegBig = -1.0e30f;   // finite stand-in for "no token seen yet"
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Plain hardware max (no NaN canonicalisation of the inputs: scores are finite or -inf here).
-__device__ __forceinline__ float vmax(float a, float b) {
-  float r;
-  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-  return r;
-}
-__device__ __forceinline__ float vmax3(float a, float b, float c) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
-}
 // max over the 4 lanes {l, l^16, l^32, l^48} with the gfx950 lane-swap instructions (vector ALU,
 // no LDS round trip): after a swap of a register with itself the pair holds both halves.
 __device__ __forceinline__ float max_over_lane_groups(float v) {
   const unsigned u = __float_as_uint(v);
   const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-  const float m16 = vmax(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const float m16 = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
   const unsigned w = __float_as_uint(m16);
   const auto c = __builtin_amdgcn_permlane32_swap(w, w, false, false);
-  return vmax(__uint_as_float(c[0]), __uint_as_float(c[1]));
+  return fmaxf(__uint_as_float(c[0]), __uint_as_float(c[1]));
 }
 __device__ __forceinline__ float sum_over_lane_groups(float v) {
   const unsigned u = __float_as_uint(v);
@@ -268,38 +257,51 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         sc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][ks], qf[mt][ks], sc[mt][1], 0, 0, 0);
       }
     }
-    // ---- phase 2: one lazy-rescale decision for the wavefront.  Whether some row's maximum
-    // has overtaken its reference by more than kLag is decided from each lane's own maximum
-    // (a row's lanes share m_run, and scaling by a positive factor keeps the order, so "some
-    // lane exceeds" and "the row maximum exceeds" are the same event); the cross-lane maximum
-    // itself is only taken when that happens, which after the first tile is rare.
-    float s[R][8], tm[R];
+    // ---- phase 2: exponent arguments against the current reference, and one lazy-rescale
+    // decision for the wavefront.  x = s * scale - m_run is needed anyway; a row has overtaken
+    // its reference by more than kLag exactly when some x of it exceeds kLag, which each lane
+    // can see in its own eight values (a row's lanes share m_run).  Only then - after the first
+    // tile that is rare - are the row maxima taken across lanes, the accumulators rescaled and
+    // the arguments recomputed against the new reference.
+    // (Every instruction that reads a matrix-core result here is an ordinary compiler-visible
+    // one: the wait states such a read needs are inserted by the compiler, which it cannot do
+    // for inline assembly.)
+    auto raw_score = [&](int mt, int e) {
+      const float v = e < 4 ? sc[mt][0][e & 3] : sc[mt][1][e & 3];
+      return (!full && e >= lane_valid) ? -INFINITY : v;
+    };
+    float x[R][8];
     bool any_up = false;
 #pragma unroll
     for (int mt = 0; mt < R; ++mt) {
+      const float neg_m = -m_run[mt];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        s[mt][e] = sc[mt][0][e];
-        s[mt][4 + e] = sc[mt][1][e];
-      }
+      for (int e = 0; e < 8; ++e) x[mt][e] = fmaf(e < 4 ? sc[mt][0][e & 3] : sc[mt][1][e & 3], scale_log2e, neg_m);
       if (!full) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (e >= lane_valid) s[mt][e] = -INFINITY;
+          if (e >= lane_valid) x[mt][e] = -INFINITY;
       }
-      tm[mt] = vmax3(vmax3(s[mt][0], s[mt][1], s[mt][2]), vmax3(s[mt][3], s[mt][4], s[mt][5]), vmax(s[mt][6], s[mt][7]));
-      any_up |= tm[mt] * scale_log2e > m_run[mt] + kLag;
+      const float tx = fmaxf(fmaxf(fmaxf(x[mt][0], x[mt][1]), fmaxf(x[mt][2], x[mt][3])),
+                             fmaxf(fmaxf(x[mt][4], x[mt][5]), fmaxf(x[mt][6], x[mt][7])));
+      any_up |= tx > kLag;
     }
     if (__any(any_up)) {
 #pragma unroll
       for (int mt = 0; mt < R; ++mt) {
-        const float m_cand = max_over_lane_groups(tm[mt]) * scale_log2e;
+        float tm = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tm = fmaxf(tm, raw_score(mt, e));
+        const float m_cand = max_over_lane_groups(tm) * scale_log2e;
         const bool up = m_cand > m_run[mt] + kLag;
         const float alpha = up ? fast_exp2(m_run[mt] - m_cand) : 1.0f;
         m_run[mt] = up ? m_cand : m_run[mt];
         l_run[mt] *= alpha;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) o[mt][nt] *= alpha;
+        const float neg_m = -m_run[mt];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[mt][e] = fmaf(raw_score(mt, e), scale_log2e, neg_m);
       }
     }
     // ---- phase 3: numerators as a bfloat16 pair, value products.
@@ -312,13 +314,12 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
     bf16x8_t p_lo[R];
 #pragma unroll
     for (int mt = 0; mt < R; ++mt) {
-      const float neg_m = -m_run[mt];
       float p[8], psum = 0.f;
       f32x8_t lo;
       uint32_t pb[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        p[e] = fast_exp2(fmaf(s[mt][e], scale_log2e, neg_m));
+        p[e] = fast_exp2(x[mt][e]);
         psum += p[e];
         pb[e] = __float_as_uint(p[e]);
         lo[e] = p[e] - __uint_as_float(pb[e] & 0xFFFF0000u);
@@ -576,7 +577,7 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
       }
 #pragma unroll
       for (int mt = 0; mt < R; ++mt) {
-        const float m_all = vmax(vmax(mw[mt][0], mw[mt][1]), vmax(mw[mt][2], mw[mt][3]));
+        const float m_all = fmaxf(fmaxf(mw[mt][0], mw[mt][1]), fmaxf(mw[mt][2], mw[mt][3]));
         float wgt[4], l_all = 0.f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
