@@ -332,3 +332,32 @@ def test_random_shapes_end_to_end(seed):
         assert r.near_ties <= 4
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("seed", range(40, 56))
+def test_random_shapes_stand_alone_entry_points(seed):
+    """The same seeded random shapes through the stand-alone entry points: every selection mode,
+    dense and sparse attention on oracle-chosen sets, per-query and shared page budgets, the
+    in-block merge."""
+    import parity_util as PU
+    w = _random_workload(seed)
+    if min(w.seq_lens) == 0:
+        w = w.replace(seq_lens=tuple(max(1, x) for x in w.seq_lens))
+    r = Rig(w)
+    try:
+        check_page_bounds(r)
+        for mode, param in ((orc.SEL_TOPK, float(w.n_active)), (orc.SEL_FRACTION, w.n_active / w.B),
+                            (orc.SEL_THRESHOLD, 0.01), (orc.SEL_MASS, 0.5)):
+            check_select_active(r, 1, mode, param)
+        check_sparse_attn(r, 0, None, None, dense=True)
+        delta = orc.locality_score(r.inp.h[1], r.inp.h[0])
+        active = [orc.active_set(delta[i * w.B:(i + 1) * w.B], orc.SEL_TOPK, float(w.n_active)) for i in range(w.batch)]
+        check_score_pages(r, 1, active, w.topk_pages)
+        _, _, union = PU.oracle_selection(r, 1, active, w.topk_pages)
+        check_sparse_attn(r, 1, active, union)
+        sets = check_score_pages_shared(r, 2, active, w.topk_pages)
+        check_sparse_attn(r, 2, active, sets)
+        _check_block_merge(r)
+        assert r.near_ties <= 6
+    finally:
+        r.close()
