@@ -257,51 +257,42 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         sc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][ks], qf[mt][ks], sc[mt][1], 0, 0, 0);
       }
     }
-    // ---- phase 2: exponent arguments against the current reference, and one lazy-rescale
-    // decision for the wavefront.  x = s * scale - m_run is needed anyway; a row has overtaken
-    // its reference by more than kLag exactly when some x of it exceeds kLag, which each lane
-    // can see in its own eight values (a row's lanes share m_run).  Only then - after the first
-    // tile that is rare - are the row maxima taken across lanes, the accumulators rescaled and
-    // the arguments recomputed against the new reference.
+    // ---- phase 2: one lazy-rescale decision for the wavefront.  Whether some row's maximum
+    // has overtaken its reference by more than kLag is decided from each lane's own maximum
+    // (a row's lanes share m_run, and scaling by a positive factor keeps the order, so "some
+    // lane exceeds" and "the row maximum exceeds" are the same event); the cross-lane maximum
+    // itself is only taken when that happens, which after the first tile is rare.
     // (Every instruction that reads a matrix-core result here is an ordinary compiler-visible
     // one: the wait states such a read needs are inserted by the compiler, which it cannot do
     // for inline assembly.)
-    auto raw_score = [&](int mt, int e) {
-      const float v = e < 4 ? sc[mt][0][e & 3] : sc[mt][1][e & 3];
-      return (!full && e >= lane_valid) ? -INFINITY : v;
-    };
-    float x[R][8];
+    float s[R][8], tm[R];
     bool any_up = false;
 #pragma unroll
     for (int mt = 0; mt < R; ++mt) {
-      const float neg_m = -m_run[mt];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[mt][e] = fmaf(e < 4 ? sc[mt][0][e & 3] : sc[mt][1][e & 3], scale_log2e, neg_m);
+      for (int e = 0; e < 4; ++e) {
+        s[mt][e] = sc[mt][0][e];
+        s[mt][4 + e] = sc[mt][1][e];
+      }
       if (!full) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (e >= lane_valid) x[mt][e] = -INFINITY;
+          if (e >= lane_valid) s[mt][e] = -INFINITY;
       }
-      const float tx = fmaxf(fmaxf(fmaxf(x[mt][0], x[mt][1]), fmaxf(x[mt][2], x[mt][3])),
-                             fmaxf(fmaxf(x[mt][4], x[mt][5]), fmaxf(x[mt][6], x[mt][7])));
-      any_up |= tx > kLag;
+      tm[mt] = fmaxf(fmaxf(fmaxf(s[mt][0], s[mt][1]), fmaxf(s[mt][2], s[mt][3])),
+                     fmaxf(fmaxf(s[mt][4], s[mt][5]), fmaxf(s[mt][6], s[mt][7])));
+      any_up |= tm[mt] * scale_log2e > m_run[mt] + kLag;
     }
     if (__any(any_up)) {
 #pragma unroll
       for (int mt = 0; mt < R; ++mt) {
-        float tm = -INFINITY;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) tm = fmaxf(tm, raw_score(mt, e));
-        const float m_cand = max_over_lane_groups(tm) * scale_log2e;
+        const float m_cand = max_over_lane_groups(tm[mt]) * scale_log2e;
         const bool up = m_cand > m_run[mt] + kLag;
         const float alpha = up ? fast_exp2(m_run[mt] - m_cand) : 1.0f;
         m_run[mt] = up ? m_cand : m_run[mt];
         l_run[mt] *= alpha;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) o[mt][nt] *= alpha;
-        const float neg_m = -m_run[mt];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[mt][e] = fmaf(raw_score(mt, e), scale_log2e, neg_m);
       }
     }
     // ---- phase 3: numerators as a bfloat16 pair, value products.
@@ -314,12 +305,13 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
     bf16x8_t p_lo[R];
 #pragma unroll
     for (int mt = 0; mt < R; ++mt) {
+      const float neg_m = -m_run[mt];
       float p[8], psum = 0.f;
       f32x8_t lo;
       uint32_t pb[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        p[e] = fast_exp2(x[mt][e]);
+        p[e] = fast_exp2(fmaf(s[mt][e], scale_log2e, neg_m));
         psum += p[e];
         pb[e] = __float_as_uint(p[e]);
         lo[e] = p[e] - __uint_as_float(pb[e] & 0xFFFF0000u);
