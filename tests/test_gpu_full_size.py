@@ -74,3 +74,39 @@ def test_shared_budget_on_long_sequences(pages):
         assert rig.near_ties <= 2
     finally:
         rig.close()
+
+
+def _random_large_workload(seed: int):
+    rng = np.random.Generator(np.random.Philox(5000 + seed))
+    B = int(rng.choice([16, 32, 64]))
+    Hkv = int(rng.choice([1, 2]))
+    G = int(rng.choice([1, 4, 7, 8]))
+    d = int(rng.choice([64, 128]))
+    g = int(rng.choice([16, 32]))
+    batch = int(rng.integers(1, 3))
+    lens = tuple(int(rng.integers(1, 60000)) for _ in range(batch))
+    dtype = "f32" if rng.integers(0, 6) == 0 else "bf16"
+    if dtype == "f32":
+        lens = tuple(min(x, 6000) for x in lens)
+    return synth.config(0, dtype=dtype).replace(B=B, Hq=Hkv * G, Hkv=Hkv, d=d, g=g, batch=batch, seq_lens=lens,
+                                                n_active=int(rng.integers(1, B + 1)), topk_pages=int(rng.integers(1, 40)),
+                                                T=3, outliers=str(rng.choice(["fixed4x8", "lognormal"])),
+                                                seed=9000 + seed, name=f"random-large-{seed}")
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_large_shapes(seed):
+    """Seeded random shapes with prefixes up to 60k tokens (the 1024-thread selection forms), up to
+    512 query rows per KV head in sparse steps (the many-row attention shape) and, now and then,
+    the float mode; a randomly chosen selection mode."""
+    w = _random_large_workload(seed)
+    rng = np.random.Generator(np.random.Philox(300 + seed))
+    mode, param = [(orc.SEL_TOPK, float(w.n_active)), (orc.SEL_FRACTION, w.n_active / w.B),
+                   (orc.SEL_THRESHOLD, 0.01), (orc.SEL_MASS, 0.5)][int(rng.integers(0, 4))]
+    rig = Rig(w)
+    try:
+        check_page_bounds(rig)
+        run_steps_end_to_end(rig, range(w.T), mode, param, w.topk_pages)
+        assert rig.near_ties <= 6
+    finally:
+        rig.close()
