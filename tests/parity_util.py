@@ -27,9 +27,11 @@ def tol(w: synth.Workload) -> float:
 class Rig:
     """A workload on the device next to its oracle state."""
 
-    def __init__(self, w: synth.Workload, device="cuda:0"):
+    def __init__(self, w: synth.Workload, device="cuda:0", mutate=None):
         self.w = w
         self.inp = synth.make_inputs(w)
+        if mutate is not None:      # edits the host inputs in place before either side sees them
+            mutate(self.inp)
         self.layer = DeviceLayer(self.inp, device)
         self.blk = DeviceBlock(self.inp, device)
         self.ctx = L.losa_create(config_of(w, max_topk_pages=w.max_pages), device)

@@ -361,3 +361,43 @@ def test_random_shapes_stand_alone_entry_points(seed):
         assert r.near_ties <= 6
     finally:
         r.close()
+
+
+def _plant_exact_ties(inp):
+    """Pages repeat with a short period (identical keys, hence identical page scores for every
+    query), and groups of block tokens share one hidden-state history (identical locality scores
+    and queries): the decisions then hinge on the tie rules alone."""
+    w = inp.w
+    rng = np.random.Generator(np.random.Philox(w.seed + 17))
+    period = int(rng.integers(1, 9))
+    for b, L in enumerate(w.seq_lens):
+        for p in range(period, L // w.g):
+            src = p % period
+            inp.K[b][p * w.g:(p + 1) * w.g] = inp.K[b][src * w.g:(src + 1) * w.g]
+    for b in range(w.batch):
+        grp = rng.choice(w.B, size=min(w.B, int(rng.integers(2, 9))), replace=False) + b * w.B
+        inp.h[:, grp[1:], :] = inp.h[:, grp[:1], :]
+        inp.q[:, grp[1:], :, :] = inp.q[:, grp[:1], :, :]
+
+
+@pytest.mark.parametrize("seed", range(60, 72))
+def test_exact_ties_follow_the_tie_rules(seed):
+    """Random shapes with exact ties planted in the page scores and the locality scores: equal
+    scores go to the smaller page / the smaller token index on both sides, so every set must be
+    identical (the near-tie allowance of the other tests is not used here)."""
+    w = _random_workload(seed)
+    if min(w.seq_lens) == 0:
+        w = w.replace(seq_lens=tuple(max(1, x) for x in w.seq_lens))
+    r = Rig(w, mutate=_plant_exact_ties)
+    try:
+        check_page_bounds(r)
+        run_steps_end_to_end(r, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+        delta = orc.locality_score(r.inp.h[1], r.inp.h[0])
+        active = [orc.active_set(delta[i * w.B:(i + 1) * w.B], orc.SEL_TOPK, float(w.n_active)) for i in range(w.batch)]
+        check_score_pages(r, 1, active, w.topk_pages)
+        check_score_pages_shared(r, 2, active, w.topk_pages)
+        for mode, param in ((orc.SEL_TOPK, float(w.n_active)), (orc.SEL_MASS, 0.5)):
+            check_select_active(r, 1, mode, param)
+        assert r.near_ties == 0
+    finally:
+        r.close()
