@@ -401,3 +401,35 @@ def test_exact_ties_follow_the_tie_rules(seed):
         assert r.near_ties == 0
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("first,count", [(0, 5), (3, 1), (7, 40), (60, -1), (10, 0), (5000, 3)])
+def test_page_bounds_of_a_page_range(first, count):
+    """losa_page_bounds over logical pages [first, first + count) of every sequence (count < 0: to
+    the end), as used when pages are appended: exactly those pages' metadata is written, bit-exact,
+    and nothing else is touched (the metadata buffer is pre-filled with a marker)."""
+    from parity_util import to_host
+    w = small_workloads()[2]                                   # ragged batch: 63, 33 and 129 pages
+    r = Rig(w)
+    try:
+        marker = 0x7B7B if w.dtype == "bf16" else 0x7B7B7B7B
+        r.layer.meta.view(torch.int16 if w.dtype == "bf16" else torch.int32).fill_(marker)
+        L.losa_page_bounds(r.ctx, r.layer.kv, first, count)
+        torch.cuda.synchronize()
+        raw = to_host(r.layer.meta)
+        meta = synth.load(raw).astype(np.float64)              # [num_pages, Hkv, 2, d]
+        untouched = np.ones(meta.shape[0], dtype=bool)
+        for b in range(w.batch):
+            kmin, kmax = r.cache.bounds[b]
+            phys = r.inp.page_indices[r.inp.page_indptr[b]: r.inp.page_indptr[b + 1]]
+            P = len(phys)
+            lo = min(first, P)
+            hi = P if count < 0 else min(first + count, P)
+            sel = np.arange(lo, max(lo, hi))
+            assert np.array_equal(meta[phys[sel], :, 0, :], kmin[sel]), f"min keys differ (seq {b})"
+            assert np.array_equal(meta[phys[sel], :, 1, :], kmax[sel]), f"max keys differ (seq {b})"
+            untouched[phys[sel]] = False
+        flat = np.asarray(raw).reshape(meta.shape[0], -1)
+        assert np.all(flat[untouched] == marker), "metadata of pages outside the range was written"
+    finally:
+        r.close()
