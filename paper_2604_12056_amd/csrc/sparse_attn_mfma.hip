@@ -125,7 +125,10 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   // fourth: this launch only serves row counts in (m_lo, m_hi] (the host may not know the count
   // and then launches both work shapes, each taking its own range)
   const bool has_rows = SPLIT_PAGES || rb * (R * 16) < M;
-  if ((M <= 0) | (chunk >= ntiles) | (!LDS_TILES && !has_rows) | (M <= m_lo) | (M > m_hi)) return;
+  // shared-tile shape: a workgroup none of whose wavefronts has rows leaves; one with some rows
+  // keeps its row-less wavefronts (they help with staging and keep the barriers)
+  const bool group_has_rows = !LDS_TILES || (int)(blockIdx.y % nrbg) * (NWAVE * R * 16) < M;
+  if ((M <= 0) | (chunk >= ntiles) | (!LDS_TILES && !has_rows) | !group_has_rows | (M <= m_lo) | (M > m_hi)) return;
   const int ntw = tfirst < ntiles ? (ntiles - 1 - tfirst) / tstep + 1 : 0;   // this wavefront's tiles
 
   bf16x8_t qf[R][KS];
@@ -744,6 +747,9 @@ static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, i
   if (rows_upper <= 32) return launch_one<D, GP, 2, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   if (rows_upper <= 48) return launch_one<D, GP, 3, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   if (rows_upper <= 64) return launch_one<D, GP, 4, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
+  // (16 rows per wavefront for up to 128 rows, so that all 8 wavefronts have work, was measured
+  // and is slower than 4 busy wavefronts of 32 rows: every wavefront reads the whole tile from
+  // LDS whatever its row count, so halving the rows halves the reuse of each operand read.)
   if (shared_tiles_enabled())
     return launch_one<D, GP, 2, false, 8, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   return launch_one<D, GP, 4, false>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);

@@ -36,7 +36,7 @@ def test_c2_ragged_batch_full():
     _run(w.replace(T=3), range(3))
 
 
-@pytest.mark.parametrize("fraction,budget", [(0.05, 1024), (0.25, 2048), (1.0, 1024)])
+@pytest.mark.parametrize("fraction,budget", [(0.05, 1024), (0.25, 2048), (0.5, 2048), (1.0, 1024)])
 def test_c4_sweep_points(fraction, budget):
     # batch 2 of the 4 sequences keeps the oracle's host memory and time modest; shapes are C4's
     w = synth.config(4, active_fraction=fraction, budget_tokens=budget)
