@@ -23,7 +23,10 @@
  *     Hq / Hkv query / KV heads, G = Hq/Hkv, H hidden size, P_b pages of sequence b.
  *     Arrays are row-major with the last index fastest.
  *   - Return value: LOSA_OK, or an error found by host-side validation before anything
- *     was enqueued (LOSA_ERR_INVALID_ARG, LOSA_ERR_UNSUPPORTED, LOSA_ERR_WORKSPACE), or
+ *     was enqueued (LOSA_ERR_INVALID_ARG: a value that makes no sense or a missing pointer;
+ *     LOSA_ERR_UNSUPPORTED: a configuration the kernels are not built for - head_dim other
+ *     than 64 / 128, page_size other than 16 / 32, block_size above 256, more than 16384
+ *     pages per sequence, hidden_size not a multiple of 8; LOSA_ERR_WORKSPACE), or
  *     LOSA_ERR_HIP if a launch was rejected.  losa_last_error gives the text.  Nothing
  *     throws or aborts.  Device-side indices (page ids, token ids) outside their range
  *     are skipped by the kernels, never dereferenced.
@@ -89,13 +92,17 @@ typedef struct {
   const void* v_pages;         /* T [num_pages, Hkv, d, g] */
   void* meta;                  /* T [num_pages, Hkv, 2, d]: row 0 elementwise min key, row 1 max key.
                                   Written by losa_page_bounds, read by losa_score_pages / losa_step. */
-  const int32_t* page_indptr;  /* [batch+1] offsets into page_indices; P_b = indptr[b+1]-indptr[b] */
+  const int32_t* page_indptr;  /* [batch+1] offsets into page_indices; sequence b lists indptr[b+1]-indptr[b]
+                                  pages, of which the first P_b = ceil(L_b / g) hold tokens and are used
+                                  (pages reserved ahead of the tokens may be listed: they are ignored) */
   const int32_t* page_indices; /* logical page p of sequence b -> physical page id */
   const int32_t* seq_lens;     /* [batch] prefix tokens L_b; the last page may be partly filled;
                                   slots past L_b may hold anything (NaN included) */
   int32_t batch;               /* host: 1..max_batch */
   int32_t num_pages;           /* host: pages in the pool (ids >= num_pages are skipped) */
-  int32_t max_seq_pages;       /* host: max_b P_b if known, else 0 (= max_pages_per_seq) */
+  int32_t max_seq_pages;       /* host: an upper bound on the pages any sequence of this call uses, if the
+                                  caller knows one (grids are sized by it), else 0 (= max_pages_per_seq).
+                                  Pages of a sequence beyond the bound are left out of every step. */
 } losa_kv;
 
 /* Bytes of device workspace losa_create needs for this configuration (0 if it is invalid). */

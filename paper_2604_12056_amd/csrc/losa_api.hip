@@ -45,7 +45,7 @@ struct losa_ctx {
   int32_t* sel_pages;
   int32_t* sel_count;
   Partials part;
-  long part_items;
+  long part_rows;           // capacity of the partial buffers in (work item, row) pairs
   long target_workgroups;   // attention workgroups aimed at per launch
   long select_round;        // selection workgroups per round (env LOSA_SELECT_ROUND; 0: from the kernel's occupancy)
   long score_round;         // scoring workgroups the machine takes in one round (env LOSA_SCORE_ROUND)
@@ -61,8 +61,9 @@ struct losa_ctx {
 
 namespace {
 
-constexpr long kTargetItems = 1024;       // capacity of the split-K partial buffers, in work items
+constexpr long kTargetItems = 1024;       // most split-K work items a sparse step may be given
 constexpr long kTargetWorkgroups = 256;   // attention workgroups aimed at per launch: one per CU
+constexpr int kSparseRows = 64;           // query rows per KV head up to which the split-pages work shape is used
 
 thread_local char g_create_err[256] = "";
 
@@ -77,27 +78,32 @@ losa_status fail(losa_ctx* ctx, losa_status st, const char* fmt, ...) {
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-bool config_problem(const losa_config* c, char* why, size_t n) {
-#define BAD(cond, msg)            \
+// LOSA_OK, or what is wrong with the configuration: LOSA_ERR_INVALID_ARG for values that make
+// no sense, LOSA_ERR_UNSUPPORTED for sensible ones outside what the kernels are built for.
+losa_status config_problem(const losa_config* c, char* why, size_t n) {
+#define BAD(cond, code, msg)      \
   if (cond) {                     \
     snprintf(why, n, "%s", msg);  \
-    return true;                  \
+    return code;                  \
   }
-  BAD(!c, "config is NULL");
-  BAD(c->max_batch < 1, "max_batch must be >= 1");
-  BAD(c->num_q_heads < 1 || c->num_kv_heads < 1, "head counts must be >= 1");
-  BAD(c->num_q_heads % c->num_kv_heads != 0, "num_q_heads must be a multiple of num_kv_heads");
-  BAD(c->head_dim != 64 && c->head_dim != 128, "head_dim must be 64 or 128");
-  BAD(c->page_size != 16 && c->page_size != 32, "page_size must be 16 or 32");
-  BAD(c->block_size < 1 || c->block_size > 256, "block_size must be in 1..256");
-  BAD(c->hidden_size < 8 || c->hidden_size % 8 != 0, "hidden_size must be a positive multiple of 8");
-  BAD(c->max_pages_per_seq < 1 || c->max_pages_per_seq > kMaxSelectPages, "max_pages_per_seq must be in 1..16384");
-  BAD(c->max_topk_pages < 1, "max_topk_pages must be >= 1");
-  BAD(c->dtype != LOSA_BF16 && c->dtype != LOSA_F32, "dtype must be LOSA_BF16 or LOSA_F32");
-  BAD(!(c->sm_scale >= 0.f) || isinf(c->sm_scale), "sm_scale must be finite and >= 0");
-  BAD((long)c->block_size * (c->num_q_heads / c->num_kv_heads) > 4096, "block_size * group size must be <= 4096");
+  const losa_status inv = LOSA_ERR_INVALID_ARG, uns = LOSA_ERR_UNSUPPORTED;
+  BAD(!c, inv, "config is NULL");
+  BAD(c->max_batch < 1, inv, "max_batch must be >= 1");
+  BAD(c->num_q_heads < 1 || c->num_kv_heads < 1, inv, "head counts must be >= 1");
+  BAD(c->num_q_heads % c->num_kv_heads != 0, inv, "num_q_heads must be a multiple of num_kv_heads");
+  BAD(c->head_dim < 1 || c->page_size < 1 || c->block_size < 1 || c->hidden_size < 1 || c->max_pages_per_seq < 1, inv,
+      "head_dim, page_size, block_size, hidden_size and max_pages_per_seq must be >= 1");
+  BAD(c->max_topk_pages < 1, inv, "max_topk_pages must be >= 1");
+  BAD(c->dtype != LOSA_BF16 && c->dtype != LOSA_F32, inv, "dtype must be LOSA_BF16 or LOSA_F32");
+  BAD(!(c->sm_scale >= 0.f) || isinf(c->sm_scale), inv, "sm_scale must be finite and >= 0");
+  BAD(c->head_dim != 64 && c->head_dim != 128, uns, "head_dim must be 64 or 128");
+  BAD(c->page_size != 16 && c->page_size != 32, uns, "page_size must be 16 or 32");
+  BAD(c->block_size > 256, uns, "block_size must be in 1..256");
+  BAD(c->hidden_size % 8 != 0, uns, "hidden_size must be a multiple of 8");
+  BAD(c->max_pages_per_seq > kMaxSelectPages, uns, "max_pages_per_seq must be in 1..16384");
+  BAD((long)c->block_size * (c->num_q_heads / c->num_kv_heads) > 4096, uns, "block_size * group size must be <= 4096");
 #undef BAD
-  return false;
+  return LOSA_OK;
 }
 
 struct Carve {
@@ -112,7 +118,7 @@ struct Carve {
 struct Layout {
   size_t delta, mask, active_idx, active_count, scores, rowmaps, tickets, sel_pages, sel_count, po, pm, pl;
   size_t entries, q_act, ucount, mrows, seq_tickets, total;
-  long part_items;
+  long part_rows;   // capacity of the split-K partial buffers, in (work item, query row) pairs
 };
 
 Layout make_layout(const losa_config* c) {
@@ -123,7 +129,14 @@ Layout make_layout(const losa_config* c) {
   const size_t rows_max = (size_t)c->block_size * G;
   const size_t heads = (size_t)c->max_batch * c->num_kv_heads;
   const size_t words = ((size_t)c->max_pages_per_seq + 31) / 32;
-  L.part_items = (long)heads > kTargetItems ? (long)heads : kTargetItems;
+  // Split-K partials: a sparse step has at most kSparseRows query rows per KV head and may use up to
+  // kTargetItems work items; a launch with more rows (the dense initialisation, large active sets)
+  // aims at kTargetWorkgroups work items (or one per head if there are more heads than that).
+  {
+    const long few = kTargetItems * (long)(rows_max < (size_t)kSparseRows ? rows_max : (size_t)kSparseRows);
+    const long many = ((long)heads > kTargetWorkgroups ? (long)heads : kTargetWorkgroups) * (long)rows_max;
+    L.part_rows = few > many ? few : many;
+  }
   L.delta = cv.take(rows * 4);
   L.mask = cv.take(rows);
   L.active_idx = cv.take(rows * 4);
@@ -133,9 +146,9 @@ Layout make_layout(const losa_config* c) {
   L.tickets = cv.take(heads * 4);
   L.sel_pages = cv.take(heads * c->max_pages_per_seq * 4);
   L.sel_count = cv.take(heads * 4);
-  L.po = cv.take((size_t)L.part_items * rows_max * c->head_dim * 4);
-  L.pm = cv.take((size_t)L.part_items * rows_max * 4);
-  L.pl = cv.take((size_t)L.part_items * rows_max * 4);
+  L.po = cv.take((size_t)L.part_rows * c->head_dim * 4);
+  L.pm = cv.take((size_t)L.part_rows * 4);
+  L.pl = cv.take((size_t)L.part_rows * 4);
   L.entries = cv.take(heads * c->max_pages_per_seq * 4);
   L.q_act = cv.take(heads * rows_max * c->head_dim * 2);
   L.ucount = cv.take(heads * 4);
@@ -185,7 +198,7 @@ losa_status check_kv(losa_ctx* ctx, const losa_kv* kv, bool need_meta, int* max_
   return LOSA_OK;
 }
 
-KvView view_of(const losa_kv* kv) {
+KvView view_of(const losa_kv* kv, int max_seq_pages) {
   KvView v;
   v.k_pages = kv->k_pages;
   v.v_pages = kv->v_pages;
@@ -194,6 +207,7 @@ KvView view_of(const losa_kv* kv) {
   v.page_indices = kv->page_indices;
   v.seq_lens = kv->seq_lens;
   v.num_pages = kv->num_pages;
+  v.seq_page_limit = max_seq_pages;
   return v;
 }
 
@@ -201,12 +215,13 @@ losa_status hip_fail(losa_ctx* ctx, const char* what, hipError_t e) {
   return fail(ctx, LOSA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
 
-// Number of equal shares a (sequence, KV head) page list of at most `upper` pages is split into.
-int pick_nchunk(const losa_ctx* ctx, int batch, int upper, int row_groups) {
+// Number of equal shares a (sequence, KV head) page list of at most `upper` pages is split into,
+// when every work item holds `part_stride` rows of partials.
+int pick_nchunk(const losa_ctx* ctx, int batch, int upper, int row_groups, int part_stride) {
   const long heads = (long)batch * ctx->sh.Hkv;
   const long tiles = (upper + (32 / ctx->sh.g) - 1) / (32 / ctx->sh.g);
   long want = ctx->target_workgroups / (heads * row_groups);
-  const long fit = ctx->part_items / heads;
+  const long fit = ctx->part_rows / (heads * part_stride);
   if (want > fit) want = fit;
   if (want > tiles) want = tiles;
   if (want < 1) want = 1;
@@ -300,7 +315,11 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   const bool both_shapes = mfma && !hinted && ctx->sh.rows_max > 64 && ctx->sh.rows_max <= 256;
   // matrix-core kernel: up to 64 rows ride in one workgroup; more rows -> groups of 4 x 64 rows
   const int row_groups = mfma ? (rows_upper <= 64 ? 1 : (ctx->sh.rows_max + 255) / 256) : (ctx->sh.rows_max + 31) / 32;
-  const int nchunk = pick_nchunk(ctx, batch, upper, mfma ? row_groups : 1);
+  // rows of partials per work item: what the host knows the row count cannot exceed
+  Partials part = ctx->part;
+  part.rows = hinted ? (rows_upper + 15) / 16 * 16 : ctx->sh.rows_max;
+  if (part.rows > ctx->sh.rows_max) part.rows = ctx->sh.rows_max;
+  const int nchunk = pick_nchunk(ctx, batch, upper, mfma ? row_groups : 1, part.rows);
   hipError_t e;
   if (mfma && !prepared) {
     StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
@@ -310,21 +329,21 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   {
     StageTimer timer(ctx, st, LOSA_STAGE_ATTN, /*bind_to_dispatch=*/mfma && !both_shapes);
     if (both_shapes) {
-      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, 64, ctx->part, nullptr, nullptr, 0, 64);
+      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, 64, part, nullptr, nullptr, 0, 64);
       if (e == hipSuccess)
-        e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, ctx->sh.rows_max, ctx->part, nullptr, nullptr,
+        e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, ctx->sh.rows_max, part, nullptr, nullptr,
                              64, 0x7fffffff);
     } else if (mfma)
-      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, rows_upper, ctx->part, timer.start(),
+      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, rows_upper, part, timer.start(),
                            timer.stop());
     else
       e = launch_attn_generic(st, ctx->cfg.dtype, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages,
-                              sel_count, cap, nchunk, ctx->part);
+                              sel_count, cap, nchunk, part);
   }
   if (e != hipSuccess) return hip_fail(ctx, "attention launch", e);
   StageTimer timer(ctx, st, LOSA_STAGE_MERGE);
   e = launch_attn_merge(st, kv, ctx->sh, batch, active_idx, active_count, sel_count, cap, nchunk,
-                        mfma ? &ctx->prep : nullptr, ctx->part, o_p, lse_p, hinted ? rows_upper : 0);
+                        mfma ? &ctx->prep : nullptr, part, o_p, lse_p, hinted ? rows_upper : 0);
   if (e != hipSuccess) return hip_fail(ctx, "attn_merge launch", e);
   return LOSA_OK;
 }
@@ -335,7 +354,7 @@ extern "C" {
 
 size_t losa_workspace_bytes(const losa_config* cfg) {
   char why[128];
-  if (config_problem(cfg, why, sizeof why)) return 0;
+  if (config_problem(cfg, why, sizeof why) != LOSA_OK) return 0;
   return make_layout(cfg).total;
 }
 
@@ -343,7 +362,8 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   if (!out) return fail(nullptr, LOSA_ERR_INVALID_ARG, "out is NULL");
   *out = nullptr;
   char why[128];
-  if (config_problem(cfg, why, sizeof why)) return fail(nullptr, LOSA_ERR_INVALID_ARG, "%s", why);
+  const losa_status cs = config_problem(cfg, why, sizeof why);
+  if (cs != LOSA_OK) return fail(nullptr, cs, "%s", why);
   const Layout L = make_layout(cfg);
   if (!workspace) return fail(nullptr, LOSA_ERR_WORKSPACE, "workspace is NULL");
   if (((uintptr_t)workspace & 255u) != 0) return fail(nullptr, LOSA_ERR_WORKSPACE, "workspace is not 256-byte aligned");
@@ -376,7 +396,8 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   ctx->part.o = (float*)(base + L.po);
   ctx->part.m = (float*)(base + L.pm);
   ctx->part.l = (float*)(base + L.pl);
-  ctx->part_items = L.part_items;
+  ctx->part.rows = sh.rows_max;
+  ctx->part_rows = L.part_rows;
   ctx->target_workgroups = kTargetWorkgroups;
   ctx->rank_in_scores = true;
   ctx->select_round = 0;
@@ -392,7 +413,7 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   if (const char* env = getenv("LOSA_RANK_IN_SCORES")) ctx->rank_in_scores = atoi(env) != 0;
   if (const char* env = getenv("LOSA_ATTN_WORKGROUPS")) {   // tuning knob: one workgroup per CU by default
     const long v = atol(env);
-    if (v >= 1 && v <= L.part_items) ctx->target_workgroups = v;
+    if (v >= 1 && v <= kTargetItems) ctx->target_workgroups = v;
   }
   ctx->prep.entries = (int32_t*)(base + L.entries);
   ctx->prep.q_act = (uint16_t*)(base + L.q_act);
@@ -484,7 +505,7 @@ losa_status losa_page_bounds(losa_ctx* ctx, void* stream, const losa_kv* kv, int
   if (num_logical_pages >= 0 && num_logical_pages < n) n = num_logical_pages;
   if (n <= 0) return LOSA_OK;
   StageTimer timer(ctx, as_stream(stream), LOSA_STAGE_BOUNDS);
-  hipError_t e = launch_page_bounds(as_stream(stream), ctx->cfg.dtype, view_of(kv), ctx->sh, kv->batch,
+  hipError_t e = launch_page_bounds(as_stream(stream), ctx->cfg.dtype, view_of(kv, msp), ctx->sh, kv->batch,
                                     first_logical_page, n);
   if (e != hipSuccess) return hip_fail(ctx, "page_bounds launch", e);
   return LOSA_OK;
@@ -505,7 +526,7 @@ losa_status losa_score_pages(losa_ctx* ctx, void* stream, const losa_kv* kv, con
   const long worst = (long)ctx->sh.rows_max * topk_pages;
   const long need = worst < msp ? worst : msp;
   if (cap < need) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap %d is below the union's worst case %ld", cap, need);
-  return score_pages_impl(ctx, as_stream(stream), view_of(kv), kv->batch, msp, q, active_idx, active_count,
+  return score_pages_impl(ctx, as_stream(stream), view_of(kv, msp), kv->batch, msp, q, active_idx, active_count,
                           topk_pages, topk_out, sel_pages, sel_count, cap, /*prepare_attn=*/false, /*rows_upper=*/0);
 }
 
@@ -524,7 +545,7 @@ losa_status losa_score_pages_shared(losa_ctx* ctx, void* stream, const losa_kv* 
   const int need = topk_pages < msp ? topk_pages : msp;
   if (cap < need) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap %d is below min(pages, topk_pages) = %d", cap, need);
   hipStream_t st = as_stream(stream);
-  const KvView view = view_of(kv);
+  const KvView view = view_of(kv, msp);
   hipError_t e;
   {
     StageTimer timer(ctx, st, LOSA_STAGE_SCORE);
@@ -552,7 +573,7 @@ losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, con
   if ((sel_pages == nullptr) != (sel_count == nullptr))
     return fail(ctx, LOSA_ERR_INVALID_ARG, "sel_pages and sel_count must both be given or both be NULL");
   if (sel_pages && cap < 1) return fail(ctx, LOSA_ERR_INVALID_ARG, "cap must be >= 1");
-  return sparse_attn_impl(ctx, as_stream(stream), view_of(kv), kv->batch, msp, q, active_idx, active_count, sel_pages,
+  return sparse_attn_impl(ctx, as_stream(stream), view_of(kv, msp), kv->batch, msp, q, active_idx, active_count, sel_pages,
                           sel_count, cap, /*rows_upper=*/0, /*prepared=*/false, (float*)o_p, lse_p);
 }
 
@@ -581,7 +602,7 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
   if (step_index < 0) return fail(ctx, LOSA_ERR_INVALID_ARG, "step_index is negative");
   if (!q || !o_p || !lse_p) return fail(ctx, LOSA_ERR_INVALID_ARG, "losa_step: NULL pointer");
   hipStream_t st = as_stream(stream);
-  const KvView view = view_of(kv);
+  const KvView view = view_of(kv, msp);
   if (dense)
     return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, nullptr, nullptr, nullptr, nullptr, 0, 0, false,
                             (float*)o_p, lse_p);

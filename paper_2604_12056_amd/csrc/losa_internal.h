@@ -18,6 +18,7 @@ struct KvView {
   const int32_t* page_indices;
   const int32_t* seq_lens;
   int32_t num_pages;
+  int32_t seq_page_limit;   // the host's upper bound on pages per sequence (grids and register tiles are sized by it)
 };
 
 // Static problem shape, passed to kernels by value.
@@ -28,11 +29,21 @@ struct Shape {
   float sm_scale;
 };
 
-// Split-K partials of the attention: item = ((b*Hkv + j)*nchunk + c), row r < rows_max.
+// Pages of sequence b that the kernels look at: those the page table lists, that hold at least
+// one of the sequence's tokens (a table may list pages reserved ahead of the tokens: their
+// metadata was never written), and that the launch was sized for.
+__device__ __forceinline__ int seq_pages(const KvView& kv, const Shape& sh, int b) {
+  const int listed = kv.page_indptr[b + 1] - kv.page_indptr[b];
+  const int filled = (kv.seq_lens[b] + sh.g - 1) >> (sh.g == 16 ? 4 : 5);   // g is 16 or 32
+  return max(0, min(min(listed, filled), min(sh.max_pages, kv.seq_page_limit)));
+}
+
+// Split-K partials of the attention: item = ((b*Hkv + j)*nchunk + c), row r < rows.
 struct Partials {
-  float* o;   // [items, rows_max, d]   un-normalised sum_t exp(s_t - m) v_t
-  float* m;   // [items, rows_max]      running max of the scaled scores
-  float* l;   // [items, rows_max]      sum_t exp(s_t - m)
+  float* o;   // [items, rows, d]   un-normalised sum_t exp(s_t - m) v_t
+  float* m;   // [items, rows]      running max of the scaled scores
+  float* l;   // [items, rows]      sum_t exp(s_t - m)
+  int rows;   // rows per item in this launch: an upper bound on the query rows of a KV head
 };
 
 // Prepared inputs of the matrix-core attention kernel, per (sequence, KV head) = `head`.

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void page_scores_kernel(KvView kv, Shape sh, c
   __shared__ float qs[RC][D];
   const int b = blockIdx.z, j = blockIdx.y, p0 = blockIdx.x * PT, tid = threadIdx.x;
   const int base = kv.page_indptr[b];
-  const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
+  const int P = seq_pages(kv, sh, b);
   const int n = min(active_count[b], sh.B);
   const int M = n * sh.G;
   if (blockIdx.x == 0 && tid == 0) aux.reset(b * sh.Hkv + j, M);
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6, l16 = lane & 15, qd = lane >> 4;
   const int base = kv.page_indptr[b];
-  const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
+  const int P = seq_pages(kv, sh, b);
   const int p0 = bx * 64 + wave * 16;
   __shared__ __attribute__((aligned(16))) float sdelta[kRankTokens];
   __shared__ int act_list[kRankTokens];
@@ -594,7 +594,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   const int n_act = min(active_count[b], sh.B);
   const int M = n_act * sh.G;
   const int base = kv.page_indptr[b];
-  const int P = max(0, min(kv.page_indptr[b + 1] - base, sh.max_pages));
+  const int P = min(seq_pages(kv, sh, b), NT * E);   // (the launcher picks NT * E >= the page limit)
   const int L = kv.seq_lens[b];
 
   if (blockIdx.x == gridDim.x - 1) {
@@ -738,10 +738,13 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   {
     // Thread t ORs bitmap word (t mod nw) of every `groups`-th row in registers, 16 independent
     // loads at a time (a loop of load-then-use would pay one memory latency per iteration),
-    // and only the per-thread results meet in LDS.  Plain loads: they cannot see stale data,
-    // since each cache line of the row bitmaps has exactly one writer in this launch and no
-    // reader before this point, the caches were invalidated when the launch began, and the
-    // writer's stores went through to memory (agent scope) before its ticket was drawn.
+    // and only the per-thread results meet in LDS.  Agent-scope atomic loads: they are served
+    // from the coherence point, not from a line this compute unit or its die's L2 holds.  The
+    // writers' stores went through to memory (agent scope) and had completed before their
+    // tickets were drawn, but the bitmap regions of two (sequence, head) pairs can share a
+    // cache line (rows * words * 4 need not be a multiple of the line), and the union
+    // workgroup of the other pair may have fetched that line while this pair's rows were
+    // still being written.
     for (int w0 = 0; w0 < wordsP; w0 += NT) {
       const int nw = min(NT, wordsP - w0);
       const int groups = NT / nw;
@@ -753,7 +756,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
 #pragma unroll
           for (int k = 0; k < 16; ++k) {
             const int rr = r0 + groups * k;
-            v[k] = maps[(size_t)min(rr, M - 1) * words + ww];
+            v[k] = __hip_atomic_load(&maps[(size_t)min(rr, M - 1) * words + ww], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           }
 #pragma unroll
           for (int k = 0; k < 16; ++k) acc |= (r0 + groups * k < M) ? v[k] : 0u;
@@ -827,7 +830,7 @@ __global__ __launch_bounds__(NT) void shared_select_kernel(KvView kv, Shape sh, 
   const int p_first = tid * E;
   if (tid < 256) rl.hist[tid] = 0u;
   const int M = min(active_count[b], sh.B) * sh.G;
-  const int P = max(0, min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages));
+  const int P = min(seq_pages(kv, sh, b), NT * E);
   if (M <= 0 || P <= 0) {
     if (tid == 0) sel_count[head] = 0;
     return;

@@ -16,9 +16,12 @@ namespace losa {
 // Both steps in one launch: one workgroup per block token computes its score; the workgroup
 // that draws the last ticket of a sequence ranks the B scores and writes the active set
 // (mode < 0: scores only - the step's scoring kernel then does the ranking itself).
-// Scores travel in agent-scope atomic stores (written through to memory) and the ranking
-// workgroup reads them with plain loads: every score has one writer in this launch, no
-// reader before the ticket, and the caches were invalidated when the launch began.
+// Scores travel in agent-scope atomic stores (written through to memory, completion awaited
+// before the ticket is drawn) and the ranking workgroup reads them with agent-scope atomic
+// loads, which are served from the coherence point, never from a line this compute unit or
+// its die's L2 fetched earlier: several sequences' scores share a 128-byte line (B * 4 < 128,
+// or any 32 tokens of a block), so a ranking workgroup of another sequence may have pulled
+// the line in before all of this sequence's scores were written.
 template <typename T>
 __global__ __launch_bounds__(256) void locality_select_kernel(const T* __restrict__ h_cur, const T* __restrict__ h_prev,
                                                               int H, int B, int mode, int n, float tau,
@@ -77,7 +80,8 @@ __global__ __launch_bounds__(256) void locality_select_kernel(const T* __restric
   if (!s_last) return;
   if (tid == 0) tickets[b] = 0;
   // ---- ranking by counting, B <= 1024: thread i handles tokens i, i+256, ...
-  for (int i = tid; i < B; i += 256) sd[i] = delta[(size_t)b * B + i];
+  for (int i = tid; i < B; i += 256)
+    sd[i] = __hip_atomic_load(&delta[(size_t)b * B + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   if (mode == LOSA_SEL_MASS) {
     // Cumulative-mass rule: scores in descending order, summed in that order in float; A is

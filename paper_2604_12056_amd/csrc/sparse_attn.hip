@@ -8,8 +8,9 @@
 // (o_p, lse_p) at the active token's row.  No float atomics anywhere: results do not
 // depend on scheduling.
 //
-// This file holds the element-type-generic kernel (vector ALUs, K/V tiles staged in LDS as
-// float); it serves the float mode and is the fallback shape for bfloat16.
+// This file holds the float-mode kernel (vector ALUs, K/V tiles staged in LDS, float64
+// accumulation) and the merge kernel both precisions share; bfloat16 inputs always take the
+// matrix-core kernel.
 #include <math.h>
 
 #include <type_traits>
@@ -46,10 +47,10 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
 
   const int chunk = blockIdx.x, j = blockIdx.y / nrb, rb = blockIdx.y % nrb, b = blockIdx.z, tid = threadIdx.x;
   const int n = active_idx ? min(active_count[b], sh.B) : sh.B;
-  const int M = n * sh.G, r0 = rb * kRowBlock;
+  const int M = min(n * sh.G, part.rows), r0 = rb * kRowBlock;
   if (r0 >= M) return;
   const int base = kv.page_indptr[b];
-  const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
+  const int P = seq_pages(kv, sh, b);
   const int L = kv.seq_lens[b];
   const int32_t* list = sel_pages ? sel_pages + ((size_t)b * sh.Hkv + j) * cap : nullptr;
   const int U = list ? min(sel_count[b * sh.Hkv + j], cap) : P;
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(256) void attn_partials_generic_kernel(
   const int r = r0 + row;
   if (r < M) {
     const size_t item = ((size_t)b * sh.Hkv + j) * nchunk + chunk;
-    const size_t prow = item * sh.rows_max + r;
+    const size_t prow = item * part.rows + r;
 #pragma unroll
     for (int k = 0; k < CPT; ++k) part.o[prow * D + sub + 8 * k] = (float)acc[k];
     if (sub == 0) {
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, co
 #pragma unroll
     for (int k = 0; k < KSPEC; ++k) {
       const int c = min(cl + CL * k, nchunk - 1);
-      const size_t prow = (item0 + c) * sh.rows_max + r;
+      const size_t prow = (item0 + c) * part.rows + r;
       pm_s[k] = part.m[prow];
       pl_s[k] = part.l[prow];
       po_s[k] = reinterpret_cast<const float4*>(part.o + prow * D)[c4];
@@ -235,10 +236,10 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, co
     U = min(ucount[b * sh.Hkv + j], sh.max_pages);
   } else {
     M = (active_idx ? min(active_count[b], sh.B) : sh.B) * sh.G;
-    const int P = min(kv.page_indptr[b + 1] - kv.page_indptr[b], sh.max_pages);
+    const int P = seq_pages(kv, sh, b);
     U = sel_count ? min(sel_count[b * sh.Hkv + j], cap) : P;
   }
-  if (r >= M) return;
+  if (r >= min(M, part.rows)) return;
   const int hg = r % sh.G;
   const int tok = tok_early;   // r < M <= B*G here, so the index above was not clamped
   if ((unsigned)tok >= (unsigned)sh.B) return;
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, co
   float mx = -INFINITY;
 #pragma unroll
   for (int k = 0; k < KSPEC; ++k) mx = fmaxf(mx, mk[k]);
-  for (int c = cl + CL * KSPEC; c < live; c += CL) mx = fmaxf(mx, part.m[(item0 + c) * sh.rows_max + r]);
+  for (int c = cl + CL * KSPEC; c < live; c += CL) mx = fmaxf(mx, part.m[(item0 + c) * part.rows + r]);
   if (c4 == 0) wmax[cl] = mx;
   __syncthreads();
   float m_tot = -INFINITY;
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, co
     }
   }
   for (int c = cl + CL * KSPEC; c < live; c += CL) {
-    const size_t prow = (item0 + c) * sh.rows_max + r;
+    const size_t prow = (item0 + c) * part.rows + r;
     const float dm = part.m[prow] - m_tot;
     const Acc w = LOG2 ? (Acc)exp2f(dm) : (Acc)exp((double)dm);
     const float4 v = reinterpret_cast<const float4*>(part.o + prow * D)[c4];
@@ -329,11 +330,7 @@ hipError_t launch_attn_generic(hipStream_t st, int dtype, const KvView& kv, cons
                                const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
                                const int32_t* sel_count, int cap, int nchunk, const Partials& part) {
   if (batch <= 0 || nchunk <= 0) return hipSuccess;
-  if (dtype == LOSA_BF16)
-    return sh.d == 128 ? launch_generic<bf16_t, 128>(st, kv, sh, batch, q, active_idx, active_count, sel_pages,
-                                                     sel_count, cap, nchunk, part)
-                       : launch_generic<bf16_t, 64>(st, kv, sh, batch, q, active_idx, active_count, sel_pages,
-                                                    sel_count, cap, nchunk, part);
+  if (dtype != LOSA_F32) return hipErrorInvalidValue;   // bfloat16 takes the matrix-core kernel
   return sh.d == 128 ? launch_generic<float, 128>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count,
                                                   cap, nchunk, part)
                      : launch_generic<float, 64>(st, kv, sh, batch, q, active_idx, active_count, sel_pages, sel_count,

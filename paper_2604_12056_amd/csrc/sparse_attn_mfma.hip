@@ -118,7 +118,7 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   };
   fetch_entries(0);
   const int U = min(U_raw, sh.max_pages);
-  const int M = min(M_raw, sh.rows_max);
+  const int M = min(M_raw, min(sh.rows_max, part.rows));   // (rows past the partial stride have nowhere to go: the host sizes it from an upper bound)
   const int ntiles = (U + PPT - 1) / PPT;
   // M <= 0: nothing active; chunk >= ntiles: this workgroup owns no tile; third: no rows for this
   // wavefront in the split-rows shape (which uses no barrier)
@@ -581,7 +581,7 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         }
         const int rg = mt * 16 + l16;
         if (rg < M) {
-          const size_t prow = item * sh.rows_max + rg;
+          const size_t prow = item * part.rows + rg;
           if (W == 0 && qd == 0) {
             part.m[prow] = m_all;
             part.l[prow] = l_all;
@@ -617,7 +617,7 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   for (int mt = 0; mt < R; ++mt) {
     const int rg = rb * (R * 16) + mt * 16 + l16;
     if (rg < M) {
-      const size_t prow = item * sh.rows_max + rg;
+      const size_t prow = item * part.rows + rg;
       if (qd == 0) {
         part.m[prow] = m_run[mt];
         part.l[prow] = l_run[mt];
@@ -646,7 +646,7 @@ __global__ __launch_bounds__(256) void attn_prepare_kernel(KvView kv, Shape sh, 
   const int gtid = blockIdx.z * 256 + threadIdx.x, gthreads = kPrepSlices * 256;
   const int head = b * sh.Hkv + j;
   const int base = kv.page_indptr[b];
-  const int P = min(kv.page_indptr[b + 1] - base, sh.max_pages);
+  const int P = seq_pages(kv, sh, b);
   const int L = kv.seq_lens[b];
   const int32_t* list = sel_pages ? sel_pages + (size_t)head * cap : nullptr;
   const int U = max(0, min(list ? min(sel_count[head], cap) : P, sh.max_pages));

@@ -256,10 +256,88 @@ def compare_state(rig: Rig, active, before_o=None, before_l=None):
         assert torch.equal(blk.lse_p[stable], before_l[stable]), "a stable row of lse_p was written"
 
 
+def gpu_union_of(rig: Rig, t: int, gpu_active, topk: int, scores, picks):
+    """The union the device builds for the given active sets, through losa_score_pages on the same
+    inputs, with every per-query pick validated against the oracle's float64 scores (only
+    near-ties of the K-th bound may differ).  Returns ({(b, j): pages}, differing picks)."""
+    w, blk = rig.w, rig.blk
+    upload_active(rig, gpu_active)
+    topk_out = torch.full((w.batch, w.B, w.Hq, topk), -7, dtype=torch.int32, device=blk.q.device)
+    L.losa_score_pages(rig.ctx, rig.layer.kv, blk.q[t], blk.active_idx, blk.active_count, topk, topk_out,
+                       blk.sel_pages, blk.sel_count, blk.cap)
+    torch.cuda.synchronize()
+    tk = topk_out.cpu().numpy()
+    sel = blk.sel_pages.cpu().numpy()
+    cnt = blk.sel_count.cpu().numpy()
+    union, differing = {}, 0
+    for b in range(w.batch):
+        Keff = min(topk, w.pages_per_seq[b])
+        for j in range(w.Hkv):
+            got_union = set()
+            for a, i in enumerate(gpu_active[b]):
+                for h in range(j * w.G, (j + 1) * w.G):
+                    got = tk[b, a, h, :Keff]
+                    differing += check_near_tie_sets(set(got.tolist()), set(picks[(b, int(i), h)].tolist()),
+                                                     scores[(b, int(i), h)], Keff, f"top pages b{b} tok{i} h{h}")
+                    got_union |= set(got.tolist())
+            U = sel[b, j, :cnt[b, j]]
+            assert list(U) == sorted(got_union), f"union b{b} kv{j} is not the union of the emitted picks"
+            union[(b, j)] = U.astype(np.int32)
+    return union, differing
+
+
+def follow_step(rig: Rig, t: int, mode: int, param: float, topk: int, gpu_mask, gpu_cnt):
+    """Advances the oracle state (rig.o_ref, rig.L_ref) by sparse step t.  The device's decisions
+    (active mask and union sizes as losa_step reported them) must be the oracle's; where a
+    near-tie made the device decide differently, the difference is validated item by item
+    against the oracle's float64 values and the oracle then follows the device's (validated)
+    active set and union, so the outputs of the step are compared in every case.
+    Returns the active sets the step used."""
+    w = rig.w
+    o_save, L_save = rig.o_ref.copy(), rig.L_ref.copy()
+    tr = orc.losa_step(rig.cache, t, rig.inp.h[t], rig.inp.h[t - 1], rig.inp.q[t], mode, param, topk, w.B, w.Hq,
+                       rig.o_ref, rig.L_ref, keep_scores=True)
+    mask = np.asarray(gpu_mask).reshape(w.batch, w.B)
+    cnt = np.asarray(gpu_cnt).reshape(w.batch, w.Hkv)
+    gpu_active = [np.nonzero(mask[b])[0].astype(np.int32) for b in range(w.batch)]
+    same_active = all(np.array_equal(gpu_active[b], tr.active[b]) for b in range(w.batch))
+    if not same_active:      # validate the device's active sets as near-ties of the n-th locality score
+        for b in range(w.batch):
+            if mode == orc.SEL_THRESHOLD:
+                for i in set(gpu_active[b].tolist()) ^ set(tr.active[b].tolist()):
+                    assert abs(tr.delta[b * w.B + i] - param) <= NEAR_TIE * max(1.0, abs(param))
+                    rig.near_ties += 1
+            elif mode == orc.SEL_MASS and len(gpu_active[b]) != len(tr.active[b]):
+                srt = np.sort(tr.delta[b * w.B:(b + 1) * w.B])[::-1]
+                k = min(len(gpu_active[b]), len(tr.active[b]))
+                assert abs(srt[:k].sum() - param * srt.sum()) <= NEAR_TIE * max(1.0, srt.sum())
+                rig.near_ties += 1
+            else:
+                rig.near_ties += check_near_tie_sets(set(gpu_active[b].tolist()), set(tr.active[b].tolist()),
+                                                     tr.delta[b * w.B:(b + 1) * w.B], len(tr.active[b]), "active set")
+        scores, picks, ref_union = oracle_selection(rig, t, gpu_active, topk)
+    else:
+        scores, picks, ref_union = tr.scores, tr.picks, tr.union
+    # The device's own union for these active sets (losa_step keeps its list in the workspace, so it
+    # is rebuilt through losa_score_pages on the same inputs): every pick validated, the sizes
+    # required to be the ones losa_step reported, the contents required to be the oracle's unless a
+    # validated near-tie changed a pick.
+    union, differing = gpu_union_of(rig, t, gpu_active, topk, scores, picks)
+    rig.near_ties += differing
+    for (b, j), I in union.items():
+        assert int(cnt[b, j]) == len(I), f"losa_step reported {cnt[b, j]} union pages for b{b} kv{j}, losa_score_pages {len(I)}"
+        if differing == 0:
+            assert np.array_equal(I, ref_union[(b, j)]), f"union b{b} kv{j} differs from the oracle's"
+    if same_active and differing == 0:
+        return gpu_active
+    rig.o_ref[:], rig.L_ref[:] = o_save, L_save
+    orc.losa_step(rig.cache, t, None, None, rig.inp.q[t], mode, param, topk, w.B, w.Hq, rig.o_ref, rig.L_ref,
+                  forced_active=gpu_active, forced_union=union)
+    return gpu_active
+
+
 def run_steps_end_to_end(rig: Rig, steps, mode: int, param: float, topk: int):
-    """losa_step over the given step indices, GPU state vs oracle state after every step.
-    If a near-tie made the GPU decide differently, the oracle is re-run with the GPU's
-    (validated) decision so later comparisons stay meaningful."""
+    """losa_step over the given step indices, GPU state vs oracle state after every step."""
     w, blk = rig.w, rig.blk
     for t in steps:
         before_o, before_l = blk.o_p.clone(), blk.lse_p.clone()
@@ -270,26 +348,5 @@ def run_steps_end_to_end(rig: Rig, steps, mode: int, param: float, topk: int):
             orc.losa_step(rig.cache, 0, None, None, rig.inp.q[0], mode, param, topk, w.B, w.Hq, rig.o_ref, rig.L_ref)
             compare_state(rig, [np.arange(w.B)] * w.batch)
             continue
-        o_save, L_save = rig.o_ref.copy(), rig.L_ref.copy()
-        tr = orc.losa_step(rig.cache, t, rig.inp.h[t], rig.inp.h[t - 1], rig.inp.q[t], mode, param, topk, w.B, w.Hq,
-                           rig.o_ref, rig.L_ref, keep_scores=True)
-        mask = blk.mask.cpu().numpy().reshape(w.batch, w.B)
-        cnt = blk.sel_count.cpu().numpy()
-        gpu_active = [np.nonzero(mask[b])[0].astype(np.int32) for b in range(w.batch)]
-        same = all(np.array_equal(gpu_active[b], tr.active[b]) for b in range(w.batch))
-        same &= all(cnt[b, j] == len(tr.union[(b, j)]) for b in range(w.batch) for j in range(w.Hkv))
-        if not same:
-            # validate the GPU's decisions as near-ties stage by stage, then follow them
-            for b in range(w.batch):
-                rig.near_ties += check_near_tie_sets(set(gpu_active[b].tolist()), set(tr.active[b].tolist()),
-                                                     tr.delta[b * w.B:(b + 1) * w.B], len(tr.active[b]), "active set")
-            rig.o_ref[:], rig.L_ref[:] = o_save, L_save
-            _, picks, union = oracle_selection(rig, t, gpu_active, topk)
-            for (b, j), I in union.items():
-                assert abs(int(cnt[b, j]) - len(I)) <= 4 * w.G, "union size differs by more than near-ties can explain"
-            orc.losa_step(rig.cache, t, None, None, rig.inp.q[t], mode, param, topk, w.B, w.Hq, rig.o_ref, rig.L_ref,
-                          forced_active=gpu_active)
-            if any(cnt[b, j] != len(union[(b, j)]) for (b, j) in union):
-                rig.near_ties += 1
-                continue        # page sets differ by a near-tie: outputs are not comparable this step
+        gpu_active = follow_step(rig, t, mode, param, topk, blk.mask.cpu().numpy(), blk.sel_count.cpu().numpy())
         compare_state(rig, gpu_active, before_o, before_l)

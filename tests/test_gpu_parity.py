@@ -167,8 +167,7 @@ def test_budget_covering_every_page_equals_dense(rig):
     """All tokens active and K >= P: the sparse path must reproduce dense prefix attention."""
     w, blk = rig.w, rig.blk
     check_page_bounds(rig)
-    if w.max_pages > rig.ctx.cfg.max_topk_pages:
-        pytest.skip("budget below the page count for this workload")
+    assert rig.ctx.cfg.max_topk_pages >= w.max_pages      # the rig's context is sized for a budget of every page
     L.losa_step(rig.ctx, rig.layer.kv, 1, blk.h[1], blk.h[0], blk.q[1], orc.SEL_FRACTION, 1.0,
                 rig.ctx.cfg.max_topk_pages, blk.o_p, blk.lse_p)
     torch.cuda.synchronize()
@@ -431,5 +430,63 @@ def test_page_bounds_of_a_page_range(first, count):
             untouched[phys[sel]] = False
         flat = np.asarray(raw).reshape(meta.shape[0], -1)
         assert np.all(flat[untouched] == marker), "metadata of pages outside the range was written"
+    finally:
+        r.close()
+
+
+def test_sequences_sharing_cache_lines_in_the_hand_overs(monkeypatch):
+    """The paper's block of 16 tokens with several sequences: the locality scores of two sequences
+    then lie in one 128-byte line (16 * 4 bytes each), and with 5 tokens x 7 heads x 100 pages the
+    pick bitmaps of two (sequence, KV head) pairs do too.  The workgroup that draws the last ticket
+    of one sequence / head must not see a stale copy of a line another one pulled in earlier.
+    Stand-alone selection in every mode, losa_step with the locality kernel's own ranking (float
+    mode takes it anyway; forced for bfloat16), and losa_step with ranking in the scoring kernel."""
+    shapes = [dict(B=16, Hq=28, Hkv=4, d=128, g=16, n_active=5, batch=6, seq_lens=(1600, 900, 333, 1599, 48, 2000),
+                   topk_pages=8, T=4, name="B16-batch6"),
+              dict(B=5, Hq=14, Hkv=2, d=64, g=16, n_active=5, batch=4, seq_lens=(1600, 1590, 1600, 1377),
+                   topk_pages=8, T=3, name="B5-G7-100-pages")]
+    for dtype in ("bf16", "f32"):
+        for rank_in_scores in ("1", "0"):
+            if dtype == "f32" and rank_in_scores == "1":
+                continue
+            monkeypatch.setenv("LOSA_RANK_IN_SCORES", rank_in_scores)
+            for kw in shapes:
+                w = synth.config(0, dtype=dtype).replace(**kw)
+                r = Rig(w)
+                try:
+                    check_page_bounds(r)
+                    for t in range(1, w.T):
+                        for mode, param in ((orc.SEL_TOPK, float(w.n_active)), (orc.SEL_THRESHOLD, 0.01), (orc.SEL_MASS, 0.5)):
+                            check_select_active(r, t, mode, param)
+                    run_steps_end_to_end(r, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+                    run_steps_end_to_end(r, [1], orc.SEL_MASS, 0.6, w.topk_pages)
+                    assert r.near_ties <= 2
+                finally:
+                    r.close()
+
+
+def test_pages_listed_beyond_the_tokens_are_ignored():
+    """A page table may list pages reserved ahead of the tokens (P_b > ceil(L_b / g)): they hold no
+    token, their metadata is never written (it is poisoned with NaN here), and they must neither be
+    scored nor selected nor attended to."""
+    from paper_2604_12056_amd.device_inputs import to_host
+    w = synth.config(2).replace(batch=2, seq_lens=(1000, 517), topk_pages=8, T=3, name="reserved-pages")
+    r = Rig(w)
+    try:
+        # shorten both sequences by some pages without touching the page table: the tail pages stay listed
+        cut = np.array([1000 - 5 * w.g - 3, 517 - 2 * w.g], dtype=np.int32)
+        r.layer.seq_lens.copy_(torch.from_numpy(cut))
+        r.layer.meta.fill_(float("nan"))
+        L.losa_page_bounds(r.ctx, r.layer.kv)
+        torch.cuda.synchronize()
+        short = w.replace(seq_lens=tuple(int(x) for x in cut))
+        r.w = short
+        r.inp.seq_lens = cut
+        r.inp.K = [k[:n] for k, n in zip(r.inp.K, cut)]
+        r.inp.V = [v[:n] for v, n in zip(r.inp.V, cut)]
+        r.cache = orc.PrefixCache(r.inp.K, r.inp.V, w.g)
+        run_steps_end_to_end(r, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+        run_steps_end_to_end(r, [1], orc.SEL_FRACTION, 1.0, r.ctx.cfg.max_topk_pages)   # budget above the page count: every real page
+        assert r.near_ties <= 2
     finally:
         r.close()
