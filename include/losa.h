@@ -113,7 +113,8 @@ size_t losa_workspace_bytes(const losa_config* cfg);
 losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspace_bytes, losa_ctx** out);
 losa_status losa_destroy(losa_ctx* ctx);
 /* Text of the last error on this context (host string owned by the context);
- * with ctx == NULL, the text of the last losa_create failure of this thread. */
+ * with ctx == NULL, the text of the last failure on this thread of a call that takes no
+ * context (losa_create, losa_select_active_static). */
 const char* losa_last_error(const losa_ctx* ctx);
 
 /* (i) Locality score and active set (eq. mse_locality; Locality Pruning).
@@ -128,6 +129,25 @@ losa_status losa_select_active(losa_ctx* ctx, void* stream, int32_t batch,
                                const void* h_cur, const void* h_prev,
                                losa_select_mode mode, float param,
                                float* delta, uint8_t* mask, int32_t* active_idx, int32_t* active_count);
+
+/* The same operation for callers that cannot allocate device memory or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It
+ * takes no context and allocates nothing, on the host or on the device: the per-sequence
+ * ticket counters its kernel needs live in a device array inside the library (16 KiB, one
+ * copy on every GPU the library runs on, held until the process ends).
+ *   dtype       : losa_dtype of h_cur / h_prev
+ *   batch       : 1..4096 (the counters the array holds); block_size : 1..1024;
+ *                 hidden_size : a multiple of 8.  Larger values: LOSA_ERR_UNSUPPORTED.
+ *   other arguments and results: exactly as losa_select_active.
+ * Runs on the GPU that is current when it is called.  The first call on a GPU looks up the
+ * array's device address (no allocation; make that call outside a graph capture).  All calls
+ * on one GPU share the array, which keeps what the last call left (zeros after a completed
+ * launch; cleared again at the start of every call): calls that overlap on one GPU - two
+ * streams, two threads - race; serialise them.  Errors: text via losa_last_error(NULL). */
+losa_status losa_select_active_static(void* stream, int32_t dtype, int32_t batch, int32_t block_size,
+                                      int32_t hidden_size, const void* h_cur, const void* h_prev,
+                                      losa_select_mode mode, float param,
+                                      float* delta, uint8_t* mask, int32_t* active_idx, int32_t* active_count);
 
 /* (ii-a) QUEST page metadata (Preliminaries, Sparse Attention Algorithms): elementwise
  * min and max key over the valid tokens of each page, for logical pages

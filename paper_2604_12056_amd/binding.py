@@ -18,7 +18,8 @@ LOSA_SEL_TOPK, LOSA_SEL_FRACTION, LOSA_SEL_THRESHOLD, LOSA_SEL_MASS = 0, 1, 2, 3
 
 EXPORTS = ["losa_workspace_bytes", "losa_create", "losa_destroy", "losa_last_error", "losa_select_active",
            "losa_page_bounds", "losa_score_pages", "losa_sparse_attn", "losa_step", "losa_profile_enable",
-           "losa_profile_read", "losa_calibration_copy", "losa_block_merge", "losa_score_pages_shared"]
+           "losa_profile_read", "losa_calibration_copy", "losa_block_merge", "losa_score_pages_shared",
+           "losa_select_active_static"]
 STAGES = ["locality", "score", "topk", "attn", "merge", "bounds", "block"]
 
 
@@ -64,6 +65,8 @@ def load_library() -> C.CDLL:
     lib.losa_last_error.argtypes = [vp]
     lib.losa_select_active.restype = C.c_int
     lib.losa_select_active.argtypes = [vp, vp, i32, p, p, C.c_int, f32, p, p, p, p]
+    lib.losa_select_active_static.restype = C.c_int
+    lib.losa_select_active_static.argtypes = [vp, i32, i32, i32, i32, p, p, C.c_int, f32, p, p, p, p]
     lib.losa_page_bounds.restype = C.c_int
     lib.losa_page_bounds.argtypes = [vp, vp, C.POINTER(losa_kv), i32, i32]
     lib.losa_score_pages.restype = C.c_int
@@ -172,6 +175,14 @@ def losa_select_active(ctx: Context, h_cur, h_prev, mode: int, param: float, del
     _check(ctx, load_library().losa_select_active(ctx.handle, _stream(stream), batch, _ptr(h_cur), _ptr(h_prev),
                                                  mode, param, _ptr(delta), _ptr(mask), _ptr(active_idx),
                                                  _ptr(active_count)))
+
+
+def losa_select_active_static(dtype: int, batch: int, block_size: int, hidden_size: int, h_cur, h_prev, mode: int,
+                              param: float, delta, mask, active_idx, active_count, stream=None):
+    """The allocation-free variant: no context, no workspace (ticket counters live in the library)."""
+    _check(None, load_library().losa_select_active_static(_stream(stream), dtype, batch, block_size, hidden_size,
+                                                         _ptr(h_cur), _ptr(h_prev), mode, param, _ptr(delta),
+                                                         _ptr(mask), _ptr(active_idx), _ptr(active_count)))
 
 
 def losa_page_bounds(ctx: Context, kv: PagedKV, first_logical_page: int = 0, num_logical_pages: int = -1, stream=None):

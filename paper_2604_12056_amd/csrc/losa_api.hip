@@ -76,6 +76,20 @@ losa_status fail(losa_ctx* ctx, losa_status st, const char* fmt, ...) {
   return st;
 }
 
+}  // namespace
+
+namespace losa {
+losa_status set_thread_error(losa_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_create_err, sizeof g_create_err, fmt, ap);
+  va_end(ap);
+  return st;
+}
+}  // namespace losa
+
+namespace {
+
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // LOSA_OK, or what is wrong with the configuration: LOSA_ERR_INVALID_ARG for values that make

@@ -55,6 +55,12 @@ struct AttnPrepared {
   int32_t* mrows;     // [heads] query rows (|A| * G)
 };
 
+// ---- losa_api.hip
+// Sets `n` ints to zero with a small fill kernel (safe to record into a captured graph).
+hipError_t launch_zero_ints(hipStream_t st, int32_t* p, int n);
+// Records the error text losa_last_error(NULL) returns on this thread; returns `st`.
+losa_status set_thread_error(losa_status st, const char* fmt, ...);
+
 // ---- select_active.hip
 // fused: score per token + ranking by the last workgroup of each sequence (tickets: [batch] ints, zero on entry)
 hipError_t launch_locality_select(hipStream_t st, int dtype, const void* h_cur, const void* h_prev, int batch, int B,

@@ -8,6 +8,10 @@
 // reduction in DPP / lane-swap steps, one LDS hop).  The ranking is by counting: with B <= 1024 tokens,
 // rank_i = #{j : delta_j > delta_i or (delta_j == delta_i and j < i)} is B compares per
 // thread out of LDS, cheaper than any sort and deterministic under ties.
+#include <math.h>
+
+#include <mutex>
+
 #include "losa_device.h"
 #include "losa_internal.h"
 
@@ -168,3 +172,90 @@ hipError_t launch_locality_delta(hipStream_t st, int dtype, const void* h_cur, c
 }
 
 }  // namespace losa
+
+// ---------------------------------------------------------------------------------------------
+// Allocation-free variant of losa_select_active: the per-sequence ticket counters, which the
+// other entry point keeps in the caller's workspace, live in a device array of this library.
+// Every GPU holds its own copy of the array (at its own address) until the process ends.
+namespace {
+
+constexpr int kStaticMaxBatch = 4096;   // sequences per call: 16 KiB of ticket counters per GPU
+constexpr int kStaticMaxBlock = 1024;   // tokens per block the ranking holds in LDS
+constexpr int kStaticMaxDevices = 64;
+
+static __device__ __align__(256) int32_t scratch[kStaticMaxBatch];
+
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kStaticMaxDevices] = {};   // device address of `scratch` per GPU; NULL: not resolved yet
+
+// The device address of `scratch` on the current GPU (in host code the array's name is only a
+// handle for this lookup, never an address a kernel may be given).
+losa_status static_scratch(int32_t** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return losa::set_thread_error(LOSA_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kStaticMaxDevices)
+    return losa::set_thread_error(LOSA_ERR_UNSUPPORTED, "device index %d outside 0..%d", dev, kStaticMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    int32_t* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return losa::set_thread_error(LOSA_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LOSA_OK;
+}
+
+}  // namespace
+
+extern "C" losa_status losa_select_active_static(void* stream, int32_t dtype, int32_t batch, int32_t block_size,
+                                                 int32_t hidden_size, const void* h_cur, const void* h_prev,
+                                                 losa_select_mode mode, float param, float* delta, uint8_t* mask,
+                                                 int32_t* active_idx, int32_t* active_count) {
+  using losa::set_thread_error;
+  if (dtype != LOSA_BF16 && dtype != LOSA_F32) return set_thread_error(LOSA_ERR_INVALID_ARG, "dtype must be LOSA_BF16 or LOSA_F32");
+  if (batch < 1 || block_size < 1 || hidden_size < 1)
+    return set_thread_error(LOSA_ERR_INVALID_ARG, "batch, block_size and hidden_size must be >= 1");
+  if (batch > kStaticMaxBatch)
+    return set_thread_error(LOSA_ERR_UNSUPPORTED, "batch %d is above the %d sequences the static scratch holds counters for",
+                            batch, kStaticMaxBatch);
+  if (block_size > kStaticMaxBlock)
+    return set_thread_error(LOSA_ERR_UNSUPPORTED, "block_size %d is above %d", block_size, kStaticMaxBlock);
+  if (hidden_size % 8 != 0) return set_thread_error(LOSA_ERR_UNSUPPORTED, "hidden_size must be a multiple of 8");
+  if (!h_cur || !h_prev || !delta || !mask || !active_idx || !active_count)
+    return set_thread_error(LOSA_ERR_INVALID_ARG, "losa_select_active_static: NULL pointer");
+  int n = 0;
+  float tau = 0.f;
+  const int B = block_size;
+  if (mode == LOSA_SEL_TOPK) {
+    if (!(param >= 0.f)) return set_thread_error(LOSA_ERR_INVALID_ARG, "top-k parameter must be >= 0");
+    n = param >= (float)B ? B : (int)param;
+  } else if (mode == LOSA_SEL_FRACTION) {
+    if (!(param >= 0.f && param <= 1.f)) return set_thread_error(LOSA_ERR_INVALID_ARG, "fraction must be in [0,1]");
+    n = (int)floorf(param * (float)B + 0.5f);
+    n = n < 1 ? 1 : (n > B ? B : n);
+  } else if (mode == LOSA_SEL_THRESHOLD) {
+    if (param != param) return set_thread_error(LOSA_ERR_INVALID_ARG, "threshold is NaN");
+    tau = param;
+  } else if (mode == LOSA_SEL_MASS) {
+    if (!(param >= 0.f && param <= 1.f)) return set_thread_error(LOSA_ERR_INVALID_ARG, "mass fraction must be in [0,1]");
+    tau = param;
+  } else {
+    return set_thread_error(LOSA_ERR_INVALID_ARG, "unknown select mode %d", (int)mode);
+  }
+  int32_t* tickets = nullptr;
+  const losa_status ss = static_scratch(&tickets);
+  if (ss != LOSA_OK) return ss;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  // The counters must start at zero.  A completed launch leaves them so, but the array is shared
+  // by every call on this GPU and an earlier launch may have been abandoned half-way; they are
+  // cleared with a fill kernel (which, unlike a memset node, replays correctly in a captured graph).
+  hipError_t e = losa::launch_zero_ints(st, tickets, batch);
+  if (e != hipSuccess) return set_thread_error(LOSA_ERR_HIP, "ticket clear launch: %s", hipGetErrorString(e));
+  e = losa::launch_locality_select(st, dtype, h_cur, h_prev, batch, B, hidden_size, (int)mode, n, tau, delta, mask,
+                                   active_idx, active_count, tickets);
+  if (e != hipSuccess) return set_thread_error(LOSA_ERR_HIP, "locality_select launch: %s", hipGetErrorString(e));
+  return LOSA_OK;
+}
