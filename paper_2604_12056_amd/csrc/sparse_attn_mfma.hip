@@ -40,6 +40,7 @@ namespace losa {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(8))) float f32x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 
 constexpr float kNegBig = -1.0e30f;   // finite stand-in for "no token seen yet"
 
@@ -80,7 +81,16 @@ struct MergeSlot {   // LDS image of one wavefront's state: O as [row tile][chan
 // so that a wavefront can issue its page-entry loads, its query loads and the two counts all
 // at once when it starts: the only dependent memory round trip left before key/value data
 // flows is entries -> pages.
-template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF, int NWAVE = 4, bool LDS_TILES = false>
+// F16V (shared-tile shape only): the value product runs in half precision.  The value tile is
+// converted bfloat16 -> half once per workgroup while it is staged into LDS (exact for
+// 2^-14 <= |v| <= 65504, truncated towards zero below that range, i.e. off by less than 2^-24,
+// and held at +-65504 above it), and the numerators go to the matrix core as ONE half-precision
+// operand (11 significant bits, round to nearest) instead of a bfloat16 hi + lo pair: a third
+// fewer matrix products per tile and no hi/lo split on the vector ALUs.  The reference point of
+// the exponentials sits 7 (log2 units) above where it would otherwise be, so that numerators use
+// the upper end of the half-precision range (they stay <= 2^15) and only values below 2^-31 of
+// a row's largest fall into its subnormals.
+template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF, int NWAVE = 4, bool LDS_TILES = false, bool F16V = false>
 __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv,
                                                         Partials part, float scale_log2e, int m_lo, int m_hi) {
   constexpr int KS = D / 32;    // k-steps of the score product
@@ -221,8 +231,28 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   // maximum overtakes its reference by more than that, which after the first tile is rare.
   // exp2(kLag) = 256 is far inside float / bfloat16 range, and (m_run, l, O) stay consistent.
   constexpr float kLag = 8.0f;
+  constexpr float kRefBias = F16V ? 7.0f : 0.0f;   // numerators are exp2(s - m_run) with m_run = reference - kRefBias
 
-  auto compute_tile = [&](Tile& t) {
+  // all score products of a tile, back to back: S^T = K_tile . Q^T for both 16-row halves
+  auto score_products = [&](const bf16x8_t (&k)[2][KS], f32x4_t (&sc)[R][2]) {
+#pragma unroll
+    for (int mt = 0; mt < R; ++mt) {
+      sc[mt][0] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+      sc[mt][1] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[0][ks], qf[mt][ks], sc[mt][0], 0, 0, 0);
+        sc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[1][ks], qf[mt][ks], sc[mt][1], 0, 0, 0);
+      }
+    }
+  };
+
+  // Softmax update and value products of a tile whose scores `sc` are given.  `between` is code
+  // the caller wants issued after the rescale decision, in the same straight-line region as the
+  // numerators (the shared-tile loop puts the NEXT tile's score products there, so that the matrix
+  // core works on them while the vector ALU takes this tile's exponentials).
+  auto softmax_values = [&](Tile& t, f32x4_t (&sc)[R][2], auto&& between, auto mfma_between_c) {
+    constexpr int MB = decltype(mfma_between_c)::value;   // matrix instructions `between` issues
     // valid tokens among this lane's 8 (tile tokens 8*qd .. 8*qd+7)
     int lane_valid;
     bool full;
@@ -233,7 +263,7 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
       full = t.nv[0] == 32;
       lane_valid = t.nv[0] - 8 * qd;
     }
-    if (!full) {
+    if (!LDS_TILES && !full) {   // (the shared-tile shape clears them once per workgroup, while staging the tile)
       // slots past the end of the sequence may hold anything: clear them in V (0 * NaN = NaN)
       const int cnt = max(0, min(8, lane_valid));
       const uint32_t m0 = cnt >= 2 ? ~0u : (cnt == 1 ? 0xFFFFu : 0u);
@@ -246,18 +276,6 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         t.v[nt].y &= m1;
         t.v[nt].z &= m2;
         t.v[nt].w &= m3;
-      }
-    }
-    // ---- phase 1: all score products back to back
-    f32x4_t sc[R][2];
-#pragma unroll
-    for (int mt = 0; mt < R; ++mt) {
-      sc[mt][0] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-      sc[mt][1] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        sc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[0][ks], qf[mt][ks], sc[mt][0], 0, 0, 0);
-        sc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][ks], qf[mt][ks], sc[mt][1], 0, 0, 0);
       }
     }
     // ---- phase 2: one lazy-rescale decision for the wavefront.  Whether some row's maximum
@@ -284,12 +302,12 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
       }
       tm[mt] = fmaxf(fmaxf(fmaxf(s[mt][0], s[mt][1]), fmaxf(s[mt][2], s[mt][3])),
                      fmaxf(fmaxf(s[mt][4], s[mt][5]), fmaxf(s[mt][6], s[mt][7])));
-      any_up |= tm[mt] * scale_log2e > m_run[mt] + kLag;
+      any_up |= tm[mt] * scale_log2e > m_run[mt] + (kLag + kRefBias);
     }
     if (__any(any_up)) {
 #pragma unroll
       for (int mt = 0; mt < R; ++mt) {
-        const float m_cand = max_over_lane_groups(tm[mt]) * scale_log2e;
+        const float m_cand = max_over_lane_groups(tm[mt]) * scale_log2e - kRefBias;
         const bool up = m_cand > m_run[mt] + kLag;
         const float alpha = up ? fast_exp2(m_run[mt] - m_cand) : 1.0f;
         m_run[mt] = up ? m_cand : m_run[mt];
@@ -305,6 +323,32 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
     // The hi products of a row tile are issued right after its numerators, so the matrix core
     // works while the vector ALU does the next row tile; all lo products come last, far from
     // the hi product that feeds the same accumulator.
+    between();
+    if constexpr (F16V) {
+      // half-precision form: one operand per row tile (the value tile in t.v is already half precision)
+#pragma unroll
+      for (int mt = 0; mt < R; ++mt) {
+        const float neg_m = -m_run[mt];
+        f32x8_t p;
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          p[e] = fast_exp2(fmaf(s[mt][e], scale_log2e, neg_m));
+          psum += p[e];
+        }
+        l_run[mt] += psum;   // the row sum is taken from the unrounded numerators
+        const f16x8_t ph = __builtin_convertvector(p, f16x8_t);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+          o[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, t.v[nt]), ph, o[mt][nt], 0, 0, 0);
+      }
+      // scheduling hint for this region: one matrix instruction, then a few vector instructions
+#pragma unroll
+      for (int i = 0; i < R * NT + MB; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // 3 VALU
+      }
+    } else {
     bf16x8_t p_lo[R];
 #pragma unroll
     for (int mt = 0; mt < R; ++mt) {
@@ -344,6 +388,12 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
       __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // 3 VALU
     }
+    }
+  };
+  auto compute_tile = [&](Tile& t) {
+    f32x4_t sc[R][2];
+    score_products(t.k, sc);
+    softmax_values(t, sc, [] {}, std::integral_constant<int, 0>{});
   };
 
   // ---- main loop: NBUF tile buffers in registers, NBUF-1 tiles of lookahead (how many: see
@@ -420,10 +470,35 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         st.v[i] = *reinterpret_cast<const u32x4_t*>(src);
       }
     };
+    // bfloat16 pair -> half pair, towards zero: exact inside the half range, never infinite
+    auto to_half2 = [](uint32_t two_bf16) -> uint32_t {
+      const auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(two_bf16 << 16), __uint_as_float(two_bf16 & 0xFFFF0000u));
+      return __builtin_bit_cast(uint32_t, h);
+    };
     auto lstore = [&](const Stage& st, int buf) {
+      // a tile that ends inside its page(s): the value slots past the end may hold anything and are
+      // cleared here, once per workgroup, so that the consumers need not look at them (0 * NaN = NaN)
+      const bool full = GP == 16 ? (st.nv[0] == 16) && (st.nv[1] == 16) : st.nv[0] == 32;
 #pragma unroll
-      for (int i = 0; i < BPW; ++i)
-        *reinterpret_cast<u32x4_t*>(lbase + buf * BUF + (wave + NWAVE * i) * 1024 + lane * 16) = st.v[i];
+      for (int i = 0; i < BPW; ++i) {
+        u32x4_t x = st.v[i];
+        if (!full && !piece_is_k[i]) {
+          // this lane's piece of a value block: 8 consecutive tokens of one channel
+          const int first = GP == 16 ? 8 * (qd & 1) : 8 * qd;
+          const int cnt = max(0, min(8, (GP == 16 && qd >= 2 ? st.nv[1] : st.nv[0]) - first));
+          x[0] &= cnt >= 2 ? ~0u : (cnt == 1 ? 0xFFFFu : 0u);
+          x[1] &= cnt >= 4 ? ~0u : (cnt == 3 ? 0xFFFFu : 0u);
+          x[2] &= cnt >= 6 ? ~0u : (cnt == 5 ? 0xFFFFu : 0u);
+          x[3] &= cnt >= 8 ? ~0u : (cnt == 7 ? 0xFFFFu : 0u);
+        }
+        if (F16V && !piece_is_k[i]) {   // (uniform over the wavefront: a block is all keys or all values)
+          x[0] = to_half2(x[0]);
+          x[1] = to_half2(x[1]);
+          x[2] = to_half2(x[2]);
+          x[3] = to_half2(x[3]);
+        }
+        *reinterpret_cast<u32x4_t*>(lbase + buf * BUF + (wave + NWAVE * i) * 1024 + lane * 16) = x;
+      }
     };
     auto lread = [&](Tile& t, int buf) {
       const unsigned char* tb_ = lbase + buf * BUF + lane * 16;
@@ -696,7 +771,7 @@ constexpr size_t shared_tile_lds_bytes() {
   return 2 * (2 * 32 * D * 2);
 }
 
-template <int D, int GP, int R, bool SPLIT, int NWAVE = 4, bool LDS_TILES = false>
+template <int D, int GP, int R, bool SPLIT, int NWAVE = 4, bool LDS_TILES = false, bool F16V = false>
 static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                              int nchunk, const Partials& part, hipEvent_t ev_start, hipEvent_t ev_stop, int m_lo,
                              int m_hi) {
@@ -711,7 +786,8 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
   // nothing is left to overlap the arithmetic with (C1: 17.9 us with 3 tiles of lookahead,
   // 15.2 us with 1).  The dense shape has arithmetic to hide behind and keeps a deeper queue.
   constexpr int NBUF = (SPLIT || LDS_TILES) ? 2 : ((D == 128 && R == 4) ? 3 : 4);
-  auto kern = attn_mfma_kernel<D, GP, R, SPLIT, NBUF, NWAVE, LDS_TILES>;
+  static_assert(!F16V || LDS_TILES, "the half-precision value product converts the tile while staging it");
+  auto kern = attn_mfma_kernel<D, GP, R, SPLIT, NBUF, NWAVE, LDS_TILES, F16V>;
   static bool attr_set = false;   // per instantiation
   if (lds_bytes > 48 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -751,7 +827,7 @@ static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, i
   // and is slower than 4 busy wavefronts of 32 rows: every wavefront reads the whole tile from
   // LDS whatever its row count, so halving the rows halves the reuse of each operand read.)
   if (shared_tiles_enabled())
-    return launch_one<D, GP, 2, false, 8, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
+    return launch_one<D, GP, 2, false, 8, true, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   return launch_one<D, GP, 4, false>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
 }
 
