@@ -50,6 +50,7 @@ struct losa_ctx {
   long select_round;        // selection workgroups per round (env LOSA_SELECT_ROUND; 0: from the kernel's occupancy)
   long score_round;         // scoring workgroups the machine takes in one round (env LOSA_SCORE_ROUND)
   bool rank_in_scores;      // losa_step lets the scoring kernel rank the locality scores (env LOSA_RANK_IN_SCORES=0: off)
+  bool union_in_attention;  // sparse steps of up to 64 rows: the attention kernel builds the union (env LOSA_UNION_IN_ATTENTION=0: off)
   AttnPrepared prep;
   char err[256];
   // measurement hooks
@@ -156,7 +157,7 @@ Layout make_layout(const losa_config* c) {
   L.active_idx = cv.take(rows * 4);
   L.active_count = cv.take((size_t)c->max_batch * 4);
   L.scores = cv.take(heads * rows_max * c->max_pages_per_seq * 4);
-  L.rowmaps = cv.take(heads * rows_max * words * 4);
+  L.rowmaps = cv.take(heads * (rows_max > (size_t)kUnionRows ? rows_max : (size_t)kUnionRows) * words * 4);   // row-major [rows_max] or word-major [kUnionRows] per word
   L.tickets = cv.take(heads * 4);
   L.sel_pages = cv.take(heads * c->max_pages_per_seq * 4);
   L.sel_count = cv.take(heads * 4);
@@ -296,7 +297,7 @@ losa_status select_active_impl(losa_ctx* ctx, hipStream_t st, int batch, const v
 losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
                              const void* q, const int32_t* active_idx, const int32_t* active_count, int topk,
                              int32_t* topk_out, int32_t* sel_pages, int32_t* sel_count, int cap, bool prepare_attn,
-                             int rows_upper, const InKernelRanking* ranking = nullptr) {
+                             int rows_upper, const InKernelRanking* ranking = nullptr, bool bitmaps_only = false) {
   const AttnPrepared* prep = prepare_attn ? &ctx->prep : nullptr;
   hipError_t e;
   {
@@ -308,7 +309,7 @@ losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   StageTimer timer(ctx, st, LOSA_STAGE_TOPK);
   e = launch_select_pages(st, kv, ctx->sh, batch, max_seq_pages, q, active_idx, active_count, ctx->scores, topk,
                           topk_out, sel_pages, sel_count, cap, ctx->rowmaps, ctx->tickets, prep, rows_upper,
-                          ctx->select_round);
+                          ctx->select_round, bitmaps_only);
   if (e != hipSuccess) return hip_fail(ctx, "select_pages launch", e);
   return LOSA_OK;
 }
@@ -316,7 +317,7 @@ losa_status score_pages_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
 losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, int batch, int max_seq_pages,
                              const void* q, const int32_t* active_idx, const int32_t* active_count,
                              const int32_t* sel_pages, const int32_t* sel_count, int cap, int rows_upper,
-                             bool prepared, float* o_p, float* lse_p) {
+                             bool prepared, float* o_p, float* lse_p, const UnionInKernel* uni = nullptr) {
   const int upper = sel_pages ? (cap < max_seq_pages ? cap : max_seq_pages) : max_seq_pages;
   const bool mfma = ctx->cfg.dtype == LOSA_BF16;
   if (!active_idx) rows_upper = ctx->sh.rows_max;   // every token is active: the count is known
@@ -349,7 +350,7 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
                              64, 0x7fffffff);
     } else if (mfma)
       e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, rows_upper, part, timer.start(),
-                           timer.stop());
+                           timer.stop(), 0, 0x7fffffff, uni);
     else
       e = launch_attn_generic(st, ctx->cfg.dtype, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages,
                               sel_count, cap, nchunk, part);
@@ -425,6 +426,8 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
     if (v >= 1) ctx->score_round = v;
   }
   if (const char* env = getenv("LOSA_RANK_IN_SCORES")) ctx->rank_in_scores = atoi(env) != 0;
+  ctx->union_in_attention = true;
+  if (const char* env = getenv("LOSA_UNION_IN_ATTENTION")) ctx->union_in_attention = atoi(env) != 0;
   if (const char* env = getenv("LOSA_ATTN_WORKGROUPS")) {   // tuning knob: one workgroup per CU by default
     const long v = atol(env);
     if (v >= 1 && v <= kTargetItems) ctx->target_workgroups = v;
@@ -647,11 +650,16 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
   // the host knows |A| in the top-n modes, so selection and attention can be shaped for n*G rows
   const bool counted = mode == LOSA_SEL_TOPK || mode == LOSA_SEL_FRACTION;
   const int rows_upper = counted ? select_count(ctx, (int)mode, param) * ctx->sh.G : 0;
+  // Up to 64 query rows per KV head and a row count the host knows: the attention workgroups build
+  // the union of the per-row picks themselves, and the selection kernel ends with the row bitmaps.
+  const bool union_in_attn = fuse_prepare && counted && rows_upper >= 1 && rows_upper <= 64 && ctx->union_in_attention;
+  const UnionInKernel uni{ctx->rowmaps, sc};
   s = score_pages_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, topk_pages, nullptr,
-                       ctx->sel_pages, sc, cap, fuse_prepare, rows_upper, rank_in_scores ? &ranking : nullptr);
+                       ctx->sel_pages, sc, cap, fuse_prepare, rows_upper, rank_in_scores ? &ranking : nullptr,
+                       union_in_attn);
   if (s != LOSA_OK) return s;
   return sparse_attn_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, ctx->sel_pages, sc,
-                          cap, rows_upper, fuse_prepare, (float*)o_p, lse_p);
+                          cap, rows_upper, fuse_prepare, (float*)o_p, lse_p, union_in_attn ? &uni : nullptr);
 }
 
 }  // extern "C"

@@ -54,6 +54,17 @@ struct AttnPrepared {
   int32_t* ucount;    // [heads] entries in the list
   int32_t* mrows;     // [heads] query rows (|A| * G)
 };
+// The other way the matrix-core kernel can get its page list (sparse steps of losa_step with at
+// most 64 query rows per KV head and a row count the host knows): the selection kernel leaves
+// only the per-row pick bitmaps, and every attention workgroup ORs them, ranks the union and
+// resolves its own pages itself while it starts up.  That takes the selection kernel's serial
+// tail (bitmap hand-over to one workgroup per head, union, list) out of the chain of launches.
+constexpr int kUnionRows = 64;   // row slots per bitmap word in that layout (the most rows the split-pages shape serves)
+struct UnionInKernel {
+  const uint32_t* rowmaps;   // [heads, words, kUnionRows] pick bitmaps, word-major: slot r of word w is row r's
+                             // word w, slots past the head's row count are zero; NULL: use AttnPrepared::entries
+  int32_t* sel_count;        // [heads] out: pages in the union (written by the head's first workgroup)
+};
 
 // ---- losa_api.hip
 // Sets `n` ints to zero with a small fill kernel (safe to record into a captured graph).
@@ -99,7 +110,8 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
                                const void* q, const int32_t* active_idx, const int32_t* active_count,
                                const float* scores, int topk, int32_t* topk_out, int32_t* sel_pages,
                                int32_t* sel_count, int cap, uint32_t* rowmaps, int32_t* tickets,
-                               const AttnPrepared* prep, int rows_hint, long workgroups_per_round);
+                               const AttnPrepared* prep, int rows_hint, long workgroups_per_round,
+                               bool bitmaps_only = false);
 
 // ---- sparse_attn.hip (element-generic kernel, merge) and sparse_attn_mfma.hip (bfloat16 matrix-core kernel)
 // Both deal the 32-token tiles of a (sequence, KV head) page list round-robin to `nchunk` work items.
@@ -114,7 +126,8 @@ hipError_t launch_attn_prepare(hipStream_t st, const KvView& kv, const Shape& sh
 // e0/e1 (both or neither): events bound to the dispatch itself, for exact kernel timing.
 hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                             int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1,
-                            int m_lo = 0, int m_hi = 0x7fffffff);   // serves (sequence, head) pairs with m_lo < rows <= m_hi
+                            int m_lo = 0, int m_hi = 0x7fffffff,   // serves (sequence, head) pairs with m_lo < rows <= m_hi
+                            const UnionInKernel* uni = nullptr);
 hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch,
                              const int32_t* active_idx, const int32_t* active_count,
                              const int32_t* sel_count, int cap, int nchunk, const AttnPrepared* prep,

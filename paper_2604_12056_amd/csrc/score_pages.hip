@@ -370,6 +370,7 @@ struct SelectOut {
   const void* q;        // query tensor (for the gather into prep.q_act)
   const int32_t* active_idx;
   bool rows_known;      // the grid has exactly one workgroup per existing row (+ the gather workgroup)
+  bool bitmaps_only;    // leave the row bitmaps to the attention kernel: no hand-over, no union, no list
 };
 
 // Inclusive suffix scan over 256 histogram buckets by one wavefront: lane l owns buckets
@@ -602,6 +603,14 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     // the dense buffer the attention kernel reads, off the path of the selection.  Indices are
     // clamped so that every load can be issued before the one it depends on has been checked.
     if (out.prep.entries == nullptr || M <= 0) return;
+    if (out.bitmaps_only) {
+      // nobody builds the union here, who would otherwise publish the row count; and the row slots
+      // past it are cleared, so that the attention kernel can OR all slots without looking at the count
+      if (tid == 0) out.prep.mrows[head] = M;
+      const int wds = (sh.max_pages + 31) / 32, spare = kUnionRows - min(M, kUnionRows);
+      uint32_t* slots = out.rowmaps + (size_t)head * wds * kUnionRows;
+      for (int i = tid; i < wds * spare; i += NT) slots[(size_t)(i / spare) * kUnionRows + (kUnionRows - spare) + i % spare] = 0u;
+    }
     constexpr int QV = 4;   // 16-byte vectors per thread per sweep
     const int vpr = sh.d / 8;
     const bf16_t* q = (const bf16_t*)out.q;
@@ -699,8 +708,14 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     // ticket".  A full agent-scope fence would also work but writes back and invalidates whole
     // L2 slices, once per workgroup.
     uint32_t* myrow = out.rowmaps + ((size_t)head * sh.rows_max + r) * words;
-    for (int w = tid; w < words; w += NT)
-      __hip_atomic_store(&myrow[w], w < WORDS ? rowbits[w] : 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (out.bitmaps_only) {   // read by the next launch: ordinary stores, into the word-major layout
+      uint32_t* slots = out.rowmaps + (size_t)head * words * kUnionRows;
+      if (r < kUnionRows)
+        for (int w = tid; w < words; w += NT) slots[(size_t)w * kUnionRows + r] = w < WORDS ? rowbits[w] : 0u;
+    } else {
+      for (int w = tid; w < words; w += NT)
+        __hip_atomic_store(&myrow[w], w < WORDS ? rowbits[w] : 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     if (r + 1 < r_end) {
       // the row bitmap has been read out (the stores above take their data at issue): clear the
       // LDS state of the next row; its first barrier (inside radix_kth) orders these writes
@@ -709,6 +724,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
       if (tid < 256) rl.hist[tid] = 0u;
     }
   }
+  if (out.bitmaps_only) return;
   const int rows_done = r_end - r_first;
   __builtin_amdgcn_s_waitcnt(0);
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
@@ -952,9 +968,11 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
                                const void* q, const int32_t* active_idx, const int32_t* active_count,
                                const float* scores, int topk, int32_t* topk_out, int32_t* sel_pages,
                                int32_t* sel_count, int cap, uint32_t* rowmaps, int32_t* tickets,
-                               const AttnPrepared* prep, int rows_hint, long workgroups_per_round) {
+                               const AttnPrepared* prep, int rows_hint, long workgroups_per_round, bool bitmaps_only) {
   if (batch <= 0) return hipSuccess;
+  if (bitmaps_only && (!prep || rows_hint < 1 || topk_out)) return hipErrorInvalidValue;
   SelectOut out;
+  out.bitmaps_only = bitmaps_only;
   out.topk_out = topk_out;
   out.sel_pages = sel_pages;
   out.sel_count = sel_count;

@@ -90,9 +90,23 @@ struct MergeSlot {   // LDS image of one wavefront's state: O as [row tile][chan
 // the exponentials sits 7 (log2 units) above where it would otherwise be, so that numerators use
 // the upper end of the half-precision range (they stay <= 2^15) and only values below 2^-31 of
 // a row's largest fall into its subnormals.
-template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF, int NWAVE = 4, bool LDS_TILES = false, bool F16V = false>
+//
+// UNION (split-pages shape only): there is no prepared page list.  The selection kernel left the
+// pick bitmap of every query row; each wavefront ORs the rows of its head (lane = bitmap word),
+// ranks the union with a popcount prefix sum, keeps words and ranks in LDS (in its own merge
+// slot, which is idle until the combine), and finds the pages of its own tiles by rank: a binary
+// search over the word ranks, a 5-step search inside the word, then one gather from the page
+// table.  One more dependent memory round trip at start-up than with a prepared list, in
+// exchange for the selection kernel's whole hand-over tail.
+constexpr int kMaxUnionWords = kMaxSelectPages / 32;
+static_assert(kUnionRows == 64, "the split-pages shape serves up to 4 row tiles of 16");
+template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF, int NWAVE = 4, bool LDS_TILES = false, bool F16V = false,
+          bool UNION = false>
 __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv,
-                                                        Partials part, float scale_log2e, int m_lo, int m_hi) {
+                                                        Partials part, float scale_log2e, int m_lo, int m_hi,
+                                                        UnionInKernel uni) {
+  static_assert(!UNION || SPLIT_PAGES, "the union is built in the kernel only in the split-pages shape");
+  static_assert(!UNION || MergeSlot<D, R>::kFloats >= 2 * kMaxUnionWords, "the union does not fit a merge slot");
   constexpr int KS = D / 32;    // k-steps of the score product
   constexpr int NT = D / 16;    // channel tiles of the output
   constexpr int PPT = 32 / GP;  // pages per 32-token tile
@@ -120,13 +134,59 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   // needs only the counts and the page entries: they are fetched first, the exit tests follow,
   // and the query fragments are requested next but not waited for until after the first tiles
   // have been requested (they arrive long before the first tile does).
-  const int U_raw = prep.ucount[head], M_raw = prep.mrows[head];
-  int pg_entry;
+  const int M_raw = prep.mrows[head];
+  int U_raw;
+  int pg_entry = 0;
   auto fetch_entries = [&](int first_local_tile) {
-    const long lp = ((long)tfirst + (long)(first_local_tile + lane / PPT) * tstep) * PPT + lane % PPT;
-    pg_entry = lp < sh.max_pages ? ent[lp] : 0;   // inside the array whatever U is; checked against U at use
+    if constexpr (!UNION) {
+      const long lp = ((long)tfirst + (long)(first_local_tile + lane / PPT) * tstep) * PPT + lane % PPT;
+      pg_entry = lp < sh.max_pages ? ent[lp] : 0;   // inside the array whatever U is; checked against U at use
+    }
   };
-  fetch_entries(0);
+  // UNION: words and ranks of the head's union, in this wavefront's own merge slot
+  [[maybe_unused]] uint32_t* u_bits = reinterpret_cast<uint32_t*>(lds + (SPLIT_PAGES ? wave : 0) * MergeSlot<D, R>::kFloats);
+  [[maybe_unused]] int* u_base = reinterpret_cast<int*>(u_bits) + kMaxUnionWords;
+  [[maybe_unused]] int u_words = 0, u_seq_len = 0, u_table = 0;
+  if constexpr (UNION) {
+    const int words = (sh.max_pages + 31) >> 5;
+    // word-major bitmaps: the kUnionRows row slots of one bitmap word are contiguous (slots past the
+    // head's row count were cleared by the selection kernel), so a lane ORs its word over all rows
+    // with a few 16-byte loads at constant offsets: one memory latency, no per-row addressing
+    const uint32_t* maps = uni.rowmaps + (size_t)head * words * kUnionRows;
+    u_table = kv.page_indptr[b];
+    u_seq_len = kv.seq_lens[b];
+    const int P = seq_pages(kv, sh, b);
+    u_words = (P + 31) >> 5;
+    int total = 0;
+    for (int g0 = 0; g0 < words; g0 += 64) {
+      const int w = g0 + lane;
+      const uint4* col = reinterpret_cast<const uint4*>(maps + (size_t)min(w, words - 1) * kUnionRows);
+      uint32_t acc = 0u;
+      {
+        uint4 v[R * 4];
+#pragma unroll
+        for (int k = 0; k < R * 4; ++k) v[k] = col[k];
+#pragma unroll
+        for (int k = 0; k < R * 4; ++k) acc |= (v[k].x | v[k].y) | (v[k].z | v[k].w);
+      }
+      // pages past the sequence's last one are never picked; the masks only keep a stale bitmap harmless
+      if (w >= u_words) acc = 0u;
+      if (w == u_words - 1 && (P & 31)) acc &= (1u << (P & 31)) - 1u;
+      const int c = __popc(acc);
+      const int incl = wave_inclusive_scan(c);
+      u_bits[w] = acc;   // w < kMaxUnionWords: max_pages <= 32 * kMaxUnionWords
+      u_base[w] = total + incl - c;
+      total += __builtin_amdgcn_readlane(incl, 63);
+    }
+    U_raw = total;
+    if (chunk == 0 && threadIdx.x == 0 && M_raw > 0) {   // for the merge kernel and the caller's diagnostics
+      prep.ucount[head] = total;
+      if (uni.sel_count) uni.sel_count[head] = total;
+    }
+  } else {
+    U_raw = prep.ucount[head];
+    fetch_entries(0);
+  }
   const int U = min(U_raw, sh.max_pages);
   const int M = min(M_raw, min(sh.rows_max, part.rows));   // (rows past the partial stride have nowhere to go: the host sizes it from an upper bound)
   const int ntiles = (U + PPT - 1) / PPT;
@@ -168,6 +228,36 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   int pg_phys = 0, pg_valid = 0;
   auto decode_entries = [&](int first_local_tile) {
     const long lp = ((long)tfirst + (long)(first_local_tile + lane / PPT) * tstep) * PPT + lane % PPT;
+    if constexpr (UNION) {
+      // the page of rank lp in the union: the last bitmap word whose rank is <= lp, then the
+      // (lp - rank)-th set bit of that word; its physical id comes from the page table
+      int page = 0;
+      const bool want = lp < U;
+      if (want) {
+        int lo = 0, hi = u_words, k = (int)lp;
+        while (hi - lo > 1) {   // (the trip count depends on u_words only: uniform over the wavefront)
+          const int mid = (lo + hi) >> 1;
+          if (u_base[mid] <= k) lo = mid; else hi = mid;
+        }
+        const uint32_t word = u_bits[lo];
+        k -= u_base[lo];
+        int pos = 0;
+#pragma unroll
+        for (int sft = 16; sft >= 1; sft >>= 1) {
+          const int c = __popc((word >> pos) & ((1u << sft) - 1u));
+          if (k >= c) {
+            k -= c;
+            pos += sft;
+          }
+        }
+        page = lo * 32 + pos;
+      }
+      const int ph = want ? kv.page_indices[u_table + page] : 0;
+      const bool ok = want && (unsigned)ph < (unsigned)kv.num_pages;
+      pg_phys = ok ? ph : 0;
+      pg_valid = ok ? max(0, min(GP, u_seq_len - page * GP)) : 0;
+      return;
+    }
     const int e = lp < U ? pg_entry : 0;
     const int ph = e & ((1 << kEntryShift) - 1);
     const bool ok = (unsigned)ph < (unsigned)kv.num_pages;
@@ -771,10 +861,10 @@ constexpr size_t shared_tile_lds_bytes() {
   return 2 * (2 * 32 * D * 2);
 }
 
-template <int D, int GP, int R, bool SPLIT, int NWAVE = 4, bool LDS_TILES = false, bool F16V = false>
+template <int D, int GP, int R, bool SPLIT, int NWAVE = 4, bool LDS_TILES = false, bool F16V = false, bool UNION = false>
 static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                              int nchunk, const Partials& part, hipEvent_t ev_start, hipEvent_t ev_stop, int m_lo,
-                             int m_hi) {
+                             int m_hi, const UnionInKernel& uni = UnionInKernel{nullptr, nullptr}) {
   static_assert(!(SPLIT && LDS_TILES) && (SPLIT ? NWAVE == 4 : true), "the split-pages combine is written for 4 wavefronts");
   const int nrbg = SPLIT ? 1 : (sh.rows_max + R * 16 * NWAVE - 1) / (R * 16 * NWAVE);
   const size_t lds_bytes = SPLIT ? 4 * MergeSlot<D, R>::kFloats * sizeof(float)
@@ -787,7 +877,7 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
   // 15.2 us with 1).  The dense shape has arithmetic to hide behind and keeps a deeper queue.
   constexpr int NBUF = (SPLIT || LDS_TILES) ? 2 : ((D == 128 && R == 4) ? 3 : 4);
   static_assert(!F16V || LDS_TILES, "the half-precision value product converts the tile while staging it");
-  auto kern = attn_mfma_kernel<D, GP, R, SPLIT, NBUF, NWAVE, LDS_TILES, F16V>;
+  auto kern = attn_mfma_kernel<D, GP, R, SPLIT, NBUF, NWAVE, LDS_TILES, F16V, UNION>;
   static bool attr_set = false;   // per instantiation
   if (lds_bytes > 48 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -799,9 +889,9 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
   dim3 grid(nchunk, sh.Hkv * nrbg, batch);
   if (ev_start && ev_stop)   // events bound to this dispatch: they read the kernel's own begin and end
     hipExtLaunchKernelGGL(kern, grid, dim3(64 * NWAVE), (uint32_t)lds_bytes, st, ev_start, ev_stop, 0, prep, nchunk,
-                          nrbg, sh, kv, part, scale_log2e, m_lo, m_hi);
+                          nrbg, sh, kv, part, scale_log2e, m_lo, m_hi, uni);
   else
-    kern<<<grid, 64 * NWAVE, lds_bytes, st>>>(prep, nchunk, nrbg, sh, kv, part, scale_log2e, m_lo, m_hi);
+    kern<<<grid, 64 * NWAVE, lds_bytes, st>>>(prep, nchunk, nrbg, sh, kv, part, scale_log2e, m_lo, m_hi, uni);
   return hipGetLastError();
 }
 
@@ -818,7 +908,14 @@ static bool shared_tiles_enabled() {
 template <int D, int GP>
 static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                             int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1, int m_lo,
-                            int m_hi) {
+                            int m_hi, const UnionInKernel* uni) {
+  if (uni && uni->rowmaps) {   // the kernel builds the union from the row bitmaps itself
+    if (rows_upper <= 16) return launch_one<D, GP, 1, true, 4, false, false, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi, *uni);
+    if (rows_upper <= 32) return launch_one<D, GP, 2, true, 4, false, false, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi, *uni);
+    if (rows_upper <= 48) return launch_one<D, GP, 3, true, 4, false, false, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi, *uni);
+    if (rows_upper <= 64) return launch_one<D, GP, 4, true, 4, false, false, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi, *uni);
+    return hipErrorInvalidValue;
+  }
   if (rows_upper <= 16) return launch_one<D, GP, 1, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   if (rows_upper <= 32) return launch_one<D, GP, 2, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   if (rows_upper <= 48) return launch_one<D, GP, 3, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
@@ -833,14 +930,14 @@ static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, i
 
 hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                             int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1, int m_lo,
-                            int m_hi) {
+                            int m_hi, const UnionInKernel* uni) {
   if (batch <= 0 || nchunk <= 0) return hipSuccess;
   if (sh.d == 128) {
-    if (sh.g == 16) return launch_dg<128, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi);
-    return launch_dg<128, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi);
+    if (sh.g == 16) return launch_dg<128, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni);
+    return launch_dg<128, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni);
   }
-  if (sh.g == 16) return launch_dg<64, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi);
-  return launch_dg<64, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi);
+  if (sh.g == 16) return launch_dg<64, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni);
+  return launch_dg<64, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni);
 }
 
 }  // namespace losa
