@@ -610,6 +610,22 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
       const int wds = (sh.max_pages + 31) / 32, spare = kUnionRows - min(M, kUnionRows);
       uint32_t* slots = out.rowmaps + (size_t)head * wds * kUnionRows;
       for (int i = tid; i < wds * spare; i += NT) slots[(size_t)(i / spare) * kUnionRows + (kUnionRows - spare) + i % spare] = 0u;
+      // ... and the head gets its page table in the form the attention kernel consumes (physical id
+      // and valid-token count of every logical page), at an address that kernel knows when it starts
+      int32_t* tab = out.prep.entries + (size_t)head * sh.max_pages;
+      for (int p0 = tid; p0 < P; p0 += NT * 4) {
+        int ph[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) ph[k] = kv.page_indices[base + min(p0 + NT * k, P - 1)];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int pg = p0 + NT * k;
+          if (pg < P) {
+            const int nv = max(0, min(sh.g, L - pg * sh.g));
+            tab[pg] = ((unsigned)ph[k] < (unsigned)kv.num_pages && ph[k] < (1 << kEntryShift)) ? (ph[k] | (nv << kEntryShift)) : 0;
+          }
+        }
+      }
     }
     constexpr int QV = 4;   // 16-byte vectors per thread per sweep
     const int vpr = sh.d / 8;

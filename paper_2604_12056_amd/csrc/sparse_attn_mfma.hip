@@ -41,6 +41,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(8))) float f32x8_t;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef uint32_t u32x4v_t __attribute__((ext_vector_type(4)));   // a plain vector value (stays in registers)
 
 constexpr float kNegBig = -1.0e30f;   // finite stand-in for "no token seen yet"
 
@@ -99,14 +100,18 @@ struct MergeSlot {   // LDS image of one wavefront's state: O as [row tile][chan
 // table.  One more dependent memory round trip at start-up than with a prepared list, in
 // exchange for the selection kernel's whole hand-over tail.
 constexpr int kMaxUnionWords = kMaxSelectPages / 32;
-static_assert(kUnionRows == 64, "the split-pages shape serves up to 4 row tiles of 16");
+constexpr int kTablePagesInLds = 2048;   // the first so many entries of a head's page table are kept in LDS
+// LDS of the split-pages shape, in floats: the four wavefronts' merge slots, then (UNION) an area the
+// workgroup fills together at start-up: each wavefront's share of the bitmap OR, and the page table.
+constexpr int kUnionShared = 4 * kMaxUnionWords + kTablePagesInLds;
 template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF, int NWAVE = 4, bool LDS_TILES = false, bool F16V = false,
           bool UNION = false>
 __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv,
                                                         Partials part, float scale_log2e, int m_lo, int m_hi,
                                                         UnionInKernel uni) {
   static_assert(!UNION || SPLIT_PAGES, "the union is built in the kernel only in the split-pages shape");
-  static_assert(!UNION || MergeSlot<D, R>::kFloats >= 2 * kMaxUnionWords, "the union does not fit a merge slot");
+  static_assert(!UNION || MergeSlot<D, R>::kFloats >= 2 * kMaxUnionWords, "the union's words and ranks do not fit a merge slot");
+  constexpr int kSlotStride = MergeSlot<D, R>::kFloats;
   constexpr int KS = D / 32;    // k-steps of the score product
   constexpr int NT = D / 16;    // channel tiles of the output
   constexpr int PPT = 32 / GP;  // pages per 32-token tile
@@ -144,37 +149,61 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
     }
   };
   // UNION: words and ranks of the head's union, in this wavefront's own merge slot
-  [[maybe_unused]] uint32_t* u_bits = reinterpret_cast<uint32_t*>(lds + (SPLIT_PAGES ? wave : 0) * MergeSlot<D, R>::kFloats);
+  // UNION: words and ranks of the head's union, in this wavefront's own merge slot; the page table and
+  // the staging of the OR in the area behind the slots
+  [[maybe_unused]] uint32_t* u_bits = reinterpret_cast<uint32_t*>(lds + (SPLIT_PAGES ? wave : 0) * kSlotStride);
   [[maybe_unused]] int* u_base = reinterpret_cast<int*>(u_bits) + kMaxUnionWords;
-  [[maybe_unused]] int u_words = 0, u_seq_len = 0, u_table = 0;
+  [[maybe_unused]] uint32_t* u_stage = reinterpret_cast<uint32_t*>(lds + 4 * kSlotStride);   // [4][kMaxUnionWords]
+  [[maybe_unused]] int* u_tab = reinterpret_cast<int*>(u_stage) + 4 * kMaxUnionWords;     // entries by logical page
+  [[maybe_unused]] int u_words = 0;
+  // pages whose entries the LDS copy holds: whole 16-byte pieces of the table, up to what fits
+  [[maybe_unused]] const int tab_lds_pages = min(sh.max_pages & ~3, kTablePagesInLds);
   if constexpr (UNION) {
+    // The four wavefronts share the start-up fetches (every workgroup of a head needs the same
+    // 16 KiB of bitmaps and 8 KiB of page table; fetched once per wavefront they cost the compute
+    // unit four times the traffic): each takes a quarter of the row slots and of the table, the
+    // pieces meet in LDS, one barrier.
     const int words = (sh.max_pages + 31) >> 5;
+    // the head's page table, written by the selection kernel at an address known here: its first
+    // kTablePagesInLds entries go to LDS, so that resolving a page needs no dependent load
+    // (pages beyond them are looked up in memory)
+    constexpr int TPW = kTablePagesInLds / 4 / 256;   // 16-byte pieces per lane per wavefront
+    u32x4v_t tabv[TPW];
+#pragma unroll
+    for (int k = 0; k < TPW; ++k) {
+      const int i4 = min(wave * (64 * TPW) + lane + 64 * k, max(sh.max_pages / 4 - 1, 0));   // clamped inside the head's table
+      tabv[k] = reinterpret_cast<const u32x4v_t*>(ent)[i4];
+    }
     // word-major bitmaps: the kUnionRows row slots of one bitmap word are contiguous (slots past the
-    // head's row count were cleared by the selection kernel), so a lane ORs its word over all rows
-    // with a few 16-byte loads at constant offsets: one memory latency, no per-row addressing
+    // head's row count were cleared by the selection kernel), so a lane ORs its word over rows with
+    // 16-byte loads at constant offsets: one memory latency, no per-row addressing
     const uint32_t* maps = uni.rowmaps + (size_t)head * words * kUnionRows;
-    u_table = kv.page_indptr[b];
-    u_seq_len = kv.seq_lens[b];
+    for (int g0 = 0; g0 < words; g0 += 64) {
+      const int w = g0 + lane;
+      const u32x4v_t* col = reinterpret_cast<const u32x4v_t*>(maps + (size_t)min(w, words - 1) * kUnionRows) + wave * R;
+      u32x4v_t v[R];
+#pragma unroll
+      for (int k = 0; k < R; ++k) v[k] = col[k];   // this wavefront's quarter of the R * 16 row slots
+      uint32_t acc = 0u;
+#pragma unroll
+      for (int k = 0; k < R; ++k) acc |= (v[k][0] | v[k][1]) | (v[k][2] | v[k][3]);
+      u_stage[wave * kMaxUnionWords + w] = acc;   // w < kMaxUnionWords: max_pages <= 32 * kMaxUnionWords
+    }
+#pragma unroll
+    for (int k = 0; k < TPW; ++k) reinterpret_cast<u32x4v_t*>(u_tab)[wave * (64 * TPW) + lane + 64 * k] = tabv[k];
     const int P = seq_pages(kv, sh, b);
     u_words = (P + 31) >> 5;
+    __syncthreads();
     int total = 0;
     for (int g0 = 0; g0 < words; g0 += 64) {
       const int w = g0 + lane;
-      const uint4* col = reinterpret_cast<const uint4*>(maps + (size_t)min(w, words - 1) * kUnionRows);
-      uint32_t acc = 0u;
-      {
-        uint4 v[R * 4];
-#pragma unroll
-        for (int k = 0; k < R * 4; ++k) v[k] = col[k];
-#pragma unroll
-        for (int k = 0; k < R * 4; ++k) acc |= (v[k].x | v[k].y) | (v[k].z | v[k].w);
-      }
+      uint32_t acc = (u_stage[w] | u_stage[kMaxUnionWords + w]) | (u_stage[2 * kMaxUnionWords + w] | u_stage[3 * kMaxUnionWords + w]);
       // pages past the sequence's last one are never picked; the masks only keep a stale bitmap harmless
       if (w >= u_words) acc = 0u;
       if (w == u_words - 1 && (P & 31)) acc &= (1u << (P & 31)) - 1u;
       const int c = __popc(acc);
       const int incl = wave_inclusive_scan(c);
-      u_bits[w] = acc;   // w < kMaxUnionWords: max_pages <= 32 * kMaxUnionWords
+      u_bits[w] = acc;
       u_base[w] = total + incl - c;
       total += __builtin_amdgcn_readlane(incl, 63);
     }
@@ -252,13 +281,11 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         }
         page = lo * 32 + pos;
       }
-      const int ph = want ? kv.page_indices[u_table + page] : 0;
-      const bool ok = want && (unsigned)ph < (unsigned)kv.num_pages;
-      pg_phys = ok ? ph : 0;
-      pg_valid = ok ? max(0, min(GP, u_seq_len - page * GP)) : 0;
-      return;
+      // (page < P <= max_pages: inside the table either way)
+      const bool from_lds = page < tab_lds_pages;
+      pg_entry = !want ? 0 : (from_lds ? u_tab[page] : ent[page]);
     }
-    const int e = lp < U ? pg_entry : 0;
+    const int e = lp < U ? pg_entry : 0;   // UNION: the entry of the page just found
     const int ph = e & ((1 << kEntryShift) - 1);
     const bool ok = (unsigned)ph < (unsigned)kv.num_pages;
     pg_phys = ok ? ph : 0;
@@ -699,7 +726,7 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
     auto publish = [&](auto wv) {
       constexpr int W = decltype(wv)::value;
       {
-        float* so = lds + W * Slot::kFloats;
+        float* so = lds + W * kSlotStride;
         float* sm = so + Slot::kOFloats;
         float* sl = sm + R * 16;
 #pragma unroll
@@ -725,13 +752,13 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         const int r = mt * 16 + l16;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          const float* sm = lds + w * Slot::kFloats + Slot::kOFloats;
+          const float* sm = lds + w * kSlotStride + Slot::kOFloats;
           mw[mt][w] = sm[r];
           lw[mt][w] = sm[R * 16 + r];
 #pragma unroll
           for (int k = 0; k < NTW; ++k)
             ov[mt][k][w] = w == W ? o[mt][W * NTW + k]
-                                  : *reinterpret_cast<const f32x4_t*>(lds + w * Slot::kFloats +
+                                  : *reinterpret_cast<const f32x4_t*>(lds + w * kSlotStride +
                                                                       ((mt * NT + W * NTW + k) * 64 + lane) * 4);
         }
       }
@@ -867,7 +894,7 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
                              int m_hi, const UnionInKernel& uni = UnionInKernel{nullptr, nullptr}) {
   static_assert(!(SPLIT && LDS_TILES) && (SPLIT ? NWAVE == 4 : true), "the split-pages combine is written for 4 wavefronts");
   const int nrbg = SPLIT ? 1 : (sh.rows_max + R * 16 * NWAVE - 1) / (R * 16 * NWAVE);
-  const size_t lds_bytes = SPLIT ? 4 * MergeSlot<D, R>::kFloats * sizeof(float)
+  const size_t lds_bytes = SPLIT ? (4 * MergeSlot<D, R>::kFloats + (UNION ? kUnionShared : 0)) * sizeof(float)
                                  : (LDS_TILES ? shared_tile_lds_bytes<D, GP>() : 0);
   // Tile buffers per wavefront (one is being computed on, the others are in flight).  The sparse
   // shape wants exactly one tile of lookahead: with more, every wavefront has its whole share
