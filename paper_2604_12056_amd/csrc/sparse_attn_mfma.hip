@@ -243,11 +243,14 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   }
   __builtin_amdgcn_sched_barrier(0);   // the query loads stay ahead of the tile loads below
 
-  float m_run[R], l_run[R];
+  float m_run[R], l_run[R], up_thr[R];   // up_thr: the raw score above which a row's reference has to move
+  const float inv_scale_log2e = 1.0f / scale_log2e;
+  [[maybe_unused]] const f16x8_t ones_h = {1, 1, 1, 1, 1, 1, 1, 1};
   f32x4_t o[R][NT];
 #pragma unroll
   for (int mt = 0; mt < R; ++mt) {
     m_run[mt] = kNegBig;
+    up_thr[mt] = -INFINITY;
     l_run[mt] = 0.f;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) o[mt][nt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
@@ -403,23 +406,21 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
     // (Every instruction that reads a matrix-core result here is an ordinary compiler-visible
     // one: the wait states such a read needs are inserted by the compiler, which it cannot do
     // for inline assembly.)
-    float s[R][8], tm[R];
+    // The scores are used where the matrix core left them (element e of the lane's 8 tokens is
+    // sc[mt][e / 4][e % 4]); the test against the reference is one compare per row tile against a
+    // threshold in score units, kept up to date with the reference.
+    float tm[R];
     bool any_up = false;
 #pragma unroll
     for (int mt = 0; mt < R; ++mt) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        s[mt][e] = sc[mt][0][e];
-        s[mt][4 + e] = sc[mt][1][e];
-      }
       if (!full) {
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-          if (e >= lane_valid) s[mt][e] = -INFINITY;
+          if (e >= lane_valid) sc[mt][e >> 2][e & 3] = -INFINITY;
       }
-      tm[mt] = fmaxf(fmaxf(fmaxf(s[mt][0], s[mt][1]), fmaxf(s[mt][2], s[mt][3])),
-                     fmaxf(fmaxf(s[mt][4], s[mt][5]), fmaxf(s[mt][6], s[mt][7])));
-      any_up |= tm[mt] * scale_log2e > m_run[mt] + (kLag + kRefBias);
+      const f32x4_t a = sc[mt][0], b = sc[mt][1];
+      tm[mt] = fmaxf(fmaxf(fmaxf(fmaxf(a[0], a[1]), a[2]), fmaxf(fmaxf(a[3], b[0]), b[1])), fmaxf(b[2], b[3]));
+      any_up |= tm[mt] > up_thr[mt];
     }
     if (__any(any_up)) {
 #pragma unroll
@@ -428,6 +429,7 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
         const bool up = m_cand > m_run[mt] + kLag;
         const float alpha = up ? fast_exp2(m_run[mt] - m_cand) : 1.0f;
         m_run[mt] = up ? m_cand : m_run[mt];
+        up_thr[mt] = (m_run[mt] + (kLag + kRefBias)) * inv_scale_log2e;
         l_run[mt] *= alpha;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) o[mt][nt] *= alpha;
@@ -447,21 +449,22 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
       for (int mt = 0; mt < R; ++mt) {
         const float neg_m = -m_run[mt];
         f32x8_t p;
-        float psum = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          p[e] = fast_exp2(fmaf(s[mt][e], scale_log2e, neg_m));
-          psum += p[e];
-        }
-        l_run[mt] += psum;   // the row sum is taken from the unrounded numerators
+        for (int e = 0; e < 8; ++e) p[e] = fast_exp2(fmaf(sc[mt][e >> 2][e & 3], scale_log2e, neg_m));
         const f16x8_t ph = __builtin_convertvector(p, f16x8_t);
+        // The row sum comes from the matrix core as well: a product with an all-ones operand sums the
+        // (rounded) numerators of the tile's 32 tokens into every element of the result, so the
+        // normaliser is exactly the sum of the weights the value product uses, and the vector ALU
+        // adds one number per row tile instead of eight.
+        const f32x4_t rs = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones_h, ph, (f32x4_t){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
           o[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, t.v[nt]), ph, o[mt][nt], 0, 0, 0);
+        l_run[mt] += rs[0];
       }
       // scheduling hint for this region: one matrix instruction, then a few vector instructions
 #pragma unroll
-      for (int i = 0; i < R * NT + MB; ++i) {
+      for (int i = 0; i < R * NT + R + MB; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
         __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // 3 VALU
       }
@@ -475,7 +478,7 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
       uint32_t pb[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        p[e] = fast_exp2(fmaf(s[mt][e], scale_log2e, neg_m));
+        p[e] = fast_exp2(fmaf(sc[mt][e >> 2][e & 3], scale_log2e, neg_m));
         psum += p[e];
         pb[e] = __float_as_uint(p[e]);
         lo[e] = p[e] - __uint_as_float(pb[e] & 0xFFFF0000u);
@@ -709,9 +712,12 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   }
   }   // !LDS_TILES
 
-  // each lane summed its own tokens; rows are spread over the 4 lane groups
+  // each lane summed its own tokens; rows are spread over the 4 lane groups (the half-precision
+  // form took whole-row sums from the matrix core: nothing to add up)
+  if constexpr (!F16V) {
 #pragma unroll
-  for (int mt = 0; mt < R; ++mt) l_run[mt] = sum_over_lane_groups(l_run[mt]);
+    for (int mt = 0; mt < R; ++mt) l_run[mt] = sum_over_lane_groups(l_run[mt]);
+  }
 
   const size_t item = ((size_t)head * nchunk + chunk);
   if (SPLIT_PAGES) {
