@@ -226,6 +226,32 @@ losa_status losa_block_merge(losa_ctx* ctx, void* stream, int32_t batch, const v
                              const void* v_b, const float* o_p, const float* lse_p, float* out, float* o_b,
                              float* lse_b);
 
+/* Tuning switches of a context: how the launches are shaped, never what they compute (results are
+ * bit-identical for every setting).  Each has a default chosen by measurement on MI355X; tests
+ * use them to drive the code paths a workload of their size would not reach.  A value takes
+ * effect with the next call on the context.
+ *   LOSA_TUNE_ATTN_WORKGROUPS   : attention workgroups aimed at per launch (default 256: one per
+ *                                 compute unit); 1..1024
+ *   LOSA_TUNE_SELECT_ROUND      : selection workgroups counted as one round of the machine; a grid
+ *                                 beyond it gives each workgroup up to four query rows (0: default)
+ *   LOSA_TUNE_SCORE_ROUND       : the same for the scoring kernel (64-page tiles per workgroup); >= 1
+ *   LOSA_TUNE_RANK_IN_SCORES    : 1 (default): inside losa_step the scoring kernel ranks the locality
+ *                                 scores itself; 0: the locality kernel does, as in losa_select_active
+ *   LOSA_TUNE_UNION_IN_ATTENTION: 1 (default): sparse steps with up to 64 query rows per KV head and a
+ *                                 row count known to the host build the union of the picked pages in the
+ *                                 attention kernel; 0: in the selection kernel, as in losa_score_pages
+ *   LOSA_TUNE_SHARED_TILES      : 1 (default): above 64 query rows per KV head eight wavefronts share
+ *                                 each key/value tile through LDS; 0: four independent wavefronts */
+typedef enum {
+  LOSA_TUNE_ATTN_WORKGROUPS = 0,
+  LOSA_TUNE_SELECT_ROUND = 1,
+  LOSA_TUNE_SCORE_ROUND = 2,
+  LOSA_TUNE_RANK_IN_SCORES = 3,
+  LOSA_TUNE_UNION_IN_ATTENTION = 4,
+  LOSA_TUNE_SHARED_TILES = 5
+} losa_tuning;
+losa_status losa_set_tuning(losa_ctx* ctx, losa_tuning knob, int64_t value);
+
 /* Measurement hooks (the paper's latency breakdown names four components: criticality
  * estimation, locality pruning, cache management, attention computation; cache management
  * costs nothing here because reuse is "do not write").  While enabled, every launch made

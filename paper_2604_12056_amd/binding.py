@@ -19,7 +19,9 @@ LOSA_SEL_TOPK, LOSA_SEL_FRACTION, LOSA_SEL_THRESHOLD, LOSA_SEL_MASS = 0, 1, 2, 3
 EXPORTS = ["losa_workspace_bytes", "losa_create", "losa_destroy", "losa_last_error", "losa_select_active",
            "losa_page_bounds", "losa_score_pages", "losa_sparse_attn", "losa_step", "losa_profile_enable",
            "losa_profile_read", "losa_calibration_copy", "losa_block_merge", "losa_score_pages_shared",
-           "losa_select_active_static"]
+           "losa_select_active_static", "losa_set_tuning"]
+(LOSA_TUNE_ATTN_WORKGROUPS, LOSA_TUNE_SELECT_ROUND, LOSA_TUNE_SCORE_ROUND, LOSA_TUNE_RANK_IN_SCORES,
+ LOSA_TUNE_UNION_IN_ATTENTION, LOSA_TUNE_SHARED_TILES) = range(6)
 STAGES = ["locality", "score", "topk", "attn", "merge", "bounds", "block"]
 
 
@@ -77,6 +79,8 @@ def load_library() -> C.CDLL:
     lib.losa_sparse_attn.argtypes = [vp, vp, C.POINTER(losa_kv), p, p, p, p, p, i32, p, p]
     lib.losa_step.restype = C.c_int
     lib.losa_step.argtypes = [vp, vp, C.POINTER(losa_kv), i32, p, p, p, C.c_int, f32, i32, p, p, p, p]
+    lib.losa_set_tuning.restype = C.c_int
+    lib.losa_set_tuning.argtypes = [vp, C.c_int, C.c_int64]
     lib.losa_profile_enable.restype = C.c_int
     lib.losa_profile_enable.argtypes = [vp, i32]
     lib.losa_profile_read.restype = C.c_int
@@ -221,6 +225,10 @@ def losa_step(ctx: Context, kv: PagedKV, step_index: int, h_cur, h_prev, q, mode
     _check(ctx, load_library().losa_step(ctx.handle, _stream(stream), C.byref(s), step_index, _ptr(h_cur),
                                         _ptr(h_prev), _ptr(q), mode, param, topk_pages, _ptr(o_p), _ptr(lse_p),
                                         _ptr(mask), _ptr(sel_count)))
+
+
+def losa_set_tuning(ctx: Context, knob: int, value: int):
+    _check(ctx, load_library().losa_set_tuning(ctx.handle, knob, int(value)))
 
 
 def losa_profile_enable(ctx: Context, enable: bool):

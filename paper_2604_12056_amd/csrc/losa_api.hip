@@ -47,10 +47,11 @@ struct losa_ctx {
   Partials part;
   long part_rows;           // capacity of the partial buffers in (work item, row) pairs
   long target_workgroups;   // attention workgroups aimed at per launch
-  long select_round;        // selection workgroups per round (env LOSA_SELECT_ROUND; 0: from the kernel's occupancy)
-  long score_round;         // scoring workgroups the machine takes in one round (env LOSA_SCORE_ROUND)
-  bool rank_in_scores;      // losa_step lets the scoring kernel rank the locality scores (env LOSA_RANK_IN_SCORES=0: off)
-  bool union_in_attention;  // sparse steps of up to 64 rows: the attention kernel builds the union (env LOSA_UNION_IN_ATTENTION=0: off)
+  long select_round;        // selection workgroups per round (0: from the kernel's occupancy)
+  long score_round;         // scoring workgroups the machine takes in one round
+  bool rank_in_scores;      // losa_step lets the scoring kernel rank the locality scores
+  bool union_in_attention;  // sparse steps of up to 64 rows: the attention kernel builds the union
+  bool shared_tiles;        // more than 64 rows: 8 wavefronts share each tile through LDS (else 4 independent ones)
   AttnPrepared prep;
   char err[256];
   // measurement hooks
@@ -344,13 +345,14 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   {
     StageTimer timer(ctx, st, LOSA_STAGE_ATTN, /*bind_to_dispatch=*/mfma && !both_shapes);
     if (both_shapes) {
-      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, 64, part, nullptr, nullptr, 0, 64);
+      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, 64, part, nullptr, nullptr, 0, 64, nullptr,
+                           ctx->shared_tiles);
       if (e == hipSuccess)
         e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, ctx->sh.rows_max, part, nullptr, nullptr,
-                             64, 0x7fffffff);
+                             64, 0x7fffffff, nullptr, ctx->shared_tiles);
     } else if (mfma)
       e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, rows_upper, part, timer.start(),
-                           timer.stop(), 0, 0x7fffffff, uni);
+                           timer.stop(), 0, 0x7fffffff, uni, ctx->shared_tiles);
     else
       e = launch_attn_generic(st, ctx->cfg.dtype, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages,
                               sel_count, cap, nchunk, part);
@@ -416,22 +418,9 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   ctx->target_workgroups = kTargetWorkgroups;
   ctx->rank_in_scores = true;
   ctx->select_round = 0;
-  if (const char* env = getenv("LOSA_SELECT_ROUND")) {
-    const long v = atol(env);
-    if (v >= 1) ctx->select_round = v;
-  }
   ctx->score_round = 5L * 256;   // about five scoring workgroups per CU are resident at once
-  if (const char* env = getenv("LOSA_SCORE_ROUND")) {
-    const long v = atol(env);
-    if (v >= 1) ctx->score_round = v;
-  }
-  if (const char* env = getenv("LOSA_RANK_IN_SCORES")) ctx->rank_in_scores = atoi(env) != 0;
   ctx->union_in_attention = true;
-  if (const char* env = getenv("LOSA_UNION_IN_ATTENTION")) ctx->union_in_attention = atoi(env) != 0;
-  if (const char* env = getenv("LOSA_ATTN_WORKGROUPS")) {   // tuning knob: one workgroup per CU by default
-    const long v = atol(env);
-    if (v >= 1 && v <= kTargetItems) ctx->target_workgroups = v;
-  }
+  ctx->shared_tiles = true;
   ctx->prep.entries = (int32_t*)(base + L.entries);
   ctx->prep.q_act = (uint16_t*)(base + L.q_act);
   ctx->prep.ucount = (int32_t*)(base + L.ucount);
@@ -446,6 +435,29 @@ losa_status losa_destroy(losa_ctx* ctx) {
   if (ctx) losa_profile_enable(ctx, 0);
   delete ctx;
   return LOSA_OK;
+}
+
+losa_status losa_set_tuning(losa_ctx* ctx, losa_tuning knob, int64_t value) {
+  if (!ctx) return LOSA_ERR_INVALID_ARG;
+  switch (knob) {
+    case LOSA_TUNE_ATTN_WORKGROUPS:
+      if (value < 1 || value > kTargetItems)
+        return fail(ctx, LOSA_ERR_INVALID_ARG, "attention workgroups must be in 1..%ld", kTargetItems);
+      ctx->target_workgroups = (long)value;
+      return LOSA_OK;
+    case LOSA_TUNE_SELECT_ROUND:
+      if (value < 0) return fail(ctx, LOSA_ERR_INVALID_ARG, "selection round must be >= 0");
+      ctx->select_round = (long)value;
+      return LOSA_OK;
+    case LOSA_TUNE_SCORE_ROUND:
+      if (value < 1) return fail(ctx, LOSA_ERR_INVALID_ARG, "scoring round must be >= 1");
+      ctx->score_round = (long)value;
+      return LOSA_OK;
+    case LOSA_TUNE_RANK_IN_SCORES: ctx->rank_in_scores = value != 0; return LOSA_OK;
+    case LOSA_TUNE_UNION_IN_ATTENTION: ctx->union_in_attention = value != 0; return LOSA_OK;
+    case LOSA_TUNE_SHARED_TILES: ctx->shared_tiles = value != 0; return LOSA_OK;
+  }
+  return fail(ctx, LOSA_ERR_INVALID_ARG, "unknown tuning switch %d", (int)knob);
 }
 
 losa_status losa_profile_enable(losa_ctx* ctx, int32_t enable) {

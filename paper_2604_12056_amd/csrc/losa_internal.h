@@ -127,7 +127,7 @@ hipError_t launch_attn_prepare(hipStream_t st, const KvView& kv, const Shape& sh
 hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                             int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1,
                             int m_lo = 0, int m_hi = 0x7fffffff,   // serves (sequence, head) pairs with m_lo < rows <= m_hi
-                            const UnionInKernel* uni = nullptr);
+                            const UnionInKernel* uni = nullptr, bool shared_tiles = true);
 hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch,
                              const int32_t* active_idx, const int32_t* active_count,
                              const int32_t* sel_count, int cap, int nchunk, const AttnPrepared* prep,

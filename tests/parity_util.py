@@ -27,7 +27,7 @@ def tol(w: synth.Workload) -> float:
 class Rig:
     """A workload on the device next to its oracle state."""
 
-    def __init__(self, w: synth.Workload, device="cuda:0", mutate=None):
+    def __init__(self, w: synth.Workload, device="cuda:0", mutate=None, tuning=None):
         self.w = w
         self.inp = synth.make_inputs(w)
         if mutate is not None:      # edits the host inputs in place before either side sees them
@@ -35,6 +35,8 @@ class Rig:
         self.layer = DeviceLayer(self.inp, device)
         self.blk = DeviceBlock(self.inp, device)
         self.ctx = L.losa_create(config_of(w, max_topk_pages=w.max_pages), device)
+        for knob, value in (tuning or {}).items():      # launch-shape switches: same results, other code paths
+            L.losa_set_tuning(self.ctx, knob, value)
         self.cache = orc.PrefixCache(self.inp.K, self.inp.V, w.g)
         rows = w.batch * w.B
         self.o_ref = np.zeros((rows, w.Hq, w.d))

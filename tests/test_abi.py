@@ -107,6 +107,12 @@ def test_workspace_checks_and_argument_validation(lib):
         assert lib.losa_step(ctx, None, C.byref(kv), 1, None, None, fake, 0, 5.0, 4, fake, fake, None, None) == inv
         assert lib.losa_step(ctx, None, C.byref(kv), -1, fake, fake, fake, 0, 5.0, 4, fake, fake, None, None) == inv
         assert lib.losa_step(ctx, None, C.byref(kv), 1, fake, fake, fake, 0, 5.0, 99, fake, fake, None, None) == inv
+        assert lib.losa_set_tuning(ctx, binding.LOSA_TUNE_ATTN_WORKGROUPS, 0) == inv
+        assert lib.losa_set_tuning(ctx, binding.LOSA_TUNE_ATTN_WORKGROUPS, 5000) == inv
+        assert lib.losa_set_tuning(ctx, binding.LOSA_TUNE_SCORE_ROUND, 0) == inv
+        assert lib.losa_set_tuning(ctx, 99, 1) == inv
+        assert lib.losa_set_tuning(ctx, binding.LOSA_TUNE_SHARED_TILES, 0) == binding.LOSA_OK
+        assert lib.losa_set_tuning(None, binding.LOSA_TUNE_SHARED_TILES, 0) == inv
     finally:
         assert lib.losa_destroy(ctx) == binding.LOSA_OK
 

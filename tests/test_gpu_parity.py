@@ -105,12 +105,11 @@ def test_losa_step_threshold_and_mass_modes(rig):
 
 
 @pytest.mark.parametrize("idx", [0, 2])
-def test_losa_step_with_ranking_in_the_locality_kernel(idx, monkeypatch):
+def test_losa_step_with_ranking_in_the_locality_kernel(idx):
     """losa_step normally lets the scoring kernel rank the locality scores; blocks larger than it
     handles (and the float mode) take the locality kernel's own ranking.  Forced here for
-    ordinary workloads, in every selection mode (the switch is read when the context is created)."""
-    monkeypatch.setenv("LOSA_RANK_IN_SCORES", "0")
-    r = Rig(small_workloads()[idx])
+    ordinary workloads, in every selection mode."""
+    r = Rig(small_workloads()[idx], tuning={L.LOSA_TUNE_RANK_IN_SCORES: 0})
     try:
         check_page_bounds(r)
         run_steps_end_to_end(r, range(r.w.T), orc.SEL_TOPK, float(r.w.n_active), r.w.topk_pages)
@@ -122,16 +121,15 @@ def test_losa_step_with_ranking_in_the_locality_kernel(idx, monkeypatch):
 
 
 @pytest.mark.parametrize("round_size", ["1", "25", "40"])
-def test_scoring_with_several_tiles_per_workgroup(round_size, monkeypatch):
+def test_scoring_with_several_tiles_per_workgroup(round_size):
     """A batch whose scoring grid would not fit the machine in one round gives each scoring
     workgroup up to four 64-page tiles.  Forced here on small workloads by shrinking what counts
-    as a round (read when the context is created): ragged tile counts, sequences shorter than a
-    workgroup's share, and more than 64 query rows per head (queries re-staged per tile)."""
-    monkeypatch.setenv("LOSA_SCORE_ROUND", round_size)
+    as a round: ragged tile counts, sequences shorter than a workgroup's share, and more than 64
+    query rows per head (queries re-staged per tile)."""
     for w in (small_workloads()[2],
               synth.config(0).replace(B=32, Hq=32, Hkv=4, d=128, g=16, n_active=12, batch=3, seq_lens=(5000, 1031, 40),
                                       topk_pages=6, T=2, name="several-tiles-96-rows")):
-        r = Rig(w)
+        r = Rig(w, tuning={L.LOSA_TUNE_SCORE_ROUND: int(round_size)})
         try:
             check_page_bounds(r)
             run_steps_end_to_end(r, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
@@ -142,14 +140,15 @@ def test_scoring_with_several_tiles_per_workgroup(round_size, monkeypatch):
 
 
 @pytest.mark.parametrize("round_size", ["1", "60", "100"])
-def test_selection_with_several_rows_per_workgroup(round_size, monkeypatch):
+@pytest.mark.parametrize("union_in_attention", [1, 0])
+def test_selection_with_several_rows_per_workgroup(round_size, union_in_attention):
     """A batch whose selection grid would not fit the machine in one round gives each selection
     workgroup up to four query rows.  Forced here on small workloads by shrinking what counts as a
-    round (read when the context is created): row counts that are not a multiple of the share,
-    every selection mode (the row count is then known only on the device), per-row lists."""
-    monkeypatch.setenv("LOSA_SELECT_ROUND", round_size)
+    round: row counts that are not a multiple of the share, every selection mode (the row count is
+    then known only on the device), per-row lists; with the union built by the attention kernel
+    (bitmaps only) and by the selection kernel."""
     for w in (small_workloads()[2], small_workloads()[4]):
-        r = Rig(w)
+        r = Rig(w, tuning={L.LOSA_TUNE_SELECT_ROUND: int(round_size), L.LOSA_TUNE_UNION_IN_ATTENTION: union_in_attention})
         try:
             check_page_bounds(r)
             run_steps_end_to_end(r, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
@@ -434,7 +433,7 @@ def test_page_bounds_of_a_page_range(first, count):
         r.close()
 
 
-def test_sequences_sharing_cache_lines_in_the_hand_overs(monkeypatch):
+def test_sequences_sharing_cache_lines_in_the_hand_overs():
     """The paper's block of 16 tokens with several sequences: the locality scores of two sequences
     then lie in one 128-byte line (16 * 4 bytes each), and with 5 tokens x 7 heads x 100 pages the
     pick bitmaps of two (sequence, KV head) pairs do too.  The workgroup that draws the last ticket
@@ -449,10 +448,10 @@ def test_sequences_sharing_cache_lines_in_the_hand_overs(monkeypatch):
         for rank_in_scores in ("1", "0"):
             if dtype == "f32" and rank_in_scores == "1":
                 continue
-            monkeypatch.setenv("LOSA_RANK_IN_SCORES", rank_in_scores)
             for kw in shapes:
                 w = synth.config(0, dtype=dtype).replace(**kw)
-                r = Rig(w)
+                # the union hand-over between workgroups only exists with the union built in the selection kernel
+                r = Rig(w, tuning={L.LOSA_TUNE_RANK_IN_SCORES: int(rank_in_scores), L.LOSA_TUNE_UNION_IN_ATTENTION: 0})
                 try:
                     check_page_bounds(r)
                     for t in range(1, w.T):
@@ -490,3 +489,24 @@ def test_pages_listed_beyond_the_tokens_are_ignored():
         assert r.near_ties <= 2
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("tuning", [{L.LOSA_TUNE_UNION_IN_ATTENTION: 0}, {L.LOSA_TUNE_SHARED_TILES: 0},
+                                    {L.LOSA_TUNE_ATTN_WORKGROUPS: 7}, {L.LOSA_TUNE_ATTN_WORKGROUPS: 1024}],
+                         ids=["union-in-selection", "independent-wavefronts", "7-workgroups", "1024-workgroups"])
+def test_launch_shape_switches_do_not_change_results(tuning):
+    """Every tuning switch of a context selects another launch shape for the same computation:
+    the union built by the selection kernel instead of the attention kernel, four independent
+    wavefronts instead of eight sharing tiles, other numbers of attention workgroups.  Each setting
+    against the oracle, on a sparse-step shape, a many-row shape and a ragged batch."""
+    many = synth.config(0).replace(B=64, Hq=32, Hkv=4, d=128, g=16, n_active=40, batch=2, seq_lens=(1900, 777),
+                                   topk_pages=6, T=3, name="many-rows")
+    for w in (small_workloads()[1], small_workloads()[2], many):
+        r = Rig(w, tuning=tuning)
+        try:
+            check_page_bounds(r)
+            run_steps_end_to_end(r, range(w.T), orc.SEL_TOPK, float(w.n_active), w.topk_pages)
+            run_steps_end_to_end(r, [1], orc.SEL_THRESHOLD, 0.01, w.topk_pages)
+            assert r.near_ties <= 2
+        finally:
+            r.close()
