@@ -9,11 +9,15 @@ Consecutive steps rotate over `--layers` independent KV caches (a model's layers
 every step reads its pages from HBM rather than from the 256 MiB last-level cache.
 
 Prints ONE JSON line.  `value` = microseconds per step per layer (lower is better), inputs
-resident in HBM.  `roofline` is for the dominant kernel (the split-K attention kernel):
-algorithmic bytes (K+V of the pages touched, active queries, partials written) divided by
-the kernel's mean duration from HIP events recorded on its stream in a second timed pass
-over the same steps.  `cpu_baseline` times the numpy oracle on a sample of the same steps.
-Also reported: dense initialisation (step 0) and page-bounds build times per layer.
+resident in HBM.  `roofline` is for the dominant kernel (the split-K attention kernel, which in
+sparse steps also builds the union of the picked pages from the per-row bitmaps while it
+starts up): algorithmic bytes (K+V of the pages touched plus the active query rows; the
+split-K partials it writes are overhead and not counted) divided by the kernel's mean
+duration from HIP events bound to its dispatch, in further passes over the same steps (the
+median of three passes is reported).  `cpu_baseline` times the numpy oracle on a sample of
+the same steps.  Also reported: dense initialisation (step 0), page-bounds build and in-block
+merge times per layer, and the read rate a plain read-only kernel reaches on this GPU over
+tiles of the page size, in order and scattered.
 """
 import argparse
 import json
@@ -46,6 +50,8 @@ def parse_args():
                          "and the page budget on configuration C4 (one JSON line per point)")
     ap.add_argument("--calibration-copy-mib", type=int, default=256,
                     help="size of the plain copy launched once as the reference for hardware byte counters")
+    ap.add_argument("--read-probe-mib", type=int, default=64,
+                    help="bytes per launch of the read-only stream probe over page-sized tiles (0: skip)")
     return ap.parse_args()
 
 
@@ -168,6 +174,31 @@ def main():
     else:
         copy_gbps = None
 
+    # ---- what a read-only stream over tiles of the page size reaches on this GPU (nothing written):
+    # 64 MiB per launch out of a 1 GiB pool, tiles in order and in a seeded random order
+    read_gbps = {}
+    if args.read_probe_mib > 0:
+        e_sz = 2 if w.dtype == "bf16" else 4
+        tile_bytes = w.g * w.d * e_sz
+        pool = torch.zeros(1 << 30, dtype=torch.uint8, device=dev)
+        n_pool = pool.numel() // tile_bytes
+        n_read = (args.read_probe_mib << 20) // tile_bytes
+        sink = torch.zeros(4096, dtype=torch.uint8, device=dev)
+        order = {"linear": torch.arange(n_pool, dtype=torch.int32),
+                 "scattered": torch.from_numpy(np.random.Generator(np.random.Philox(4242)).permutation(n_pool).astype(np.int32))}
+        for name, ids in order.items():
+            ids = ids.to(dev)
+            launches = n_pool // n_read
+            for rep in range(2):          # the second sweep over the pool is the timed one
+                e0, e1 = ev(), ev()
+                e0.record()
+                for k in range(launches):
+                    L.losa_calibration_read(pool, tile_bytes, ids[k * n_read:(k + 1) * n_read], sink)
+                e1.record()
+                torch.cuda.synchronize()
+            read_gbps[name] = launches * n_read * tile_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del pool, sink
+
     # ---- once per block: page bounds, then the dense initialisation (step 0) of every layer.
     # Each is run eagerly once (results needed below), then timed as one graph replay over all
     # layers so that host launch cost does not count.
@@ -285,20 +316,18 @@ def main():
         warm_us = e0.elapsed_time(e1) * 1e3 / args.steps
         del warm_graph
 
-    # ---- second pass over the same steps with per-kernel events on the launch stream
+    # ---- further passes over the same steps with per-kernel events on the launch stream
     # (events bound to a dispatch add packets around it, and how much that stretches a kernel varies
-    # from box to box and pass to pass: the pass is run three times and the one with the shortest
-    # mean attention launch is reported, i.e. the least disturbed average, never a single launch)
-    stage_us = None
+    # from box to box and pass to pass: three passes, the median of their per-stage means is reported)
+    passes = []
     for _ in range(3):
         L.losa_profile_enable(ctx, True)
         run_steps(args.steps, args.warmup, record=True)
         torch.cuda.synchronize()
         ms, cnt = L.losa_profile_read(ctx)
         L.losa_profile_enable(ctx, False)
-        cand = {k: (ms[k] * 1e3 / cnt[k] if cnt[k] else None) for k in ms}
-        if stage_us is None or (cand["attn"] is not None and cand["attn"] < stage_us["attn"]):
-            stage_us = cand
+        passes.append({k: (ms[k] * 1e3 / cnt[k] if cnt[k] else None) for k in ms})
+    stage_us = {k: (float(np.median([p_[k] for p_ in passes])) if passes[0][k] is not None else None) for k in passes[0]}
 
     # ---- algorithmic bytes of the attention kernel per launch
     e = 2 if w.dtype == "bf16" else 4
@@ -337,6 +366,7 @@ def main():
         "us_per_step_spread": spread,
         "warm_single_layer_us_per_step": round(warm_us, 3) if warm_us is not None else None,
         "measured_copy_GBps": round(copy_gbps, 1) if copy_gbps is not None else None,
+        "measured_read_GBps": {k: round(v, 1) for k, v in read_gbps.items()} or None,
         "step_hbm_GBps": round(step_bytes / (us_per_step * 1e-6) / 1e9, 1),
         "step_bytes": int(step_bytes),
         "union_pages_per_kv_head": round(pages_per_launch / (w.batch * w.Hkv), 1),
@@ -359,10 +389,14 @@ def main():
         "block_merge_us_per_layer": round(block_merge_us, 2),
         "page_bounds_us_per_layer": round(bounds_us, 2),
         "page_bounds_GBps": round((sum(w.seq_lens) * w.Hkv * w.d * e + meta_bytes) / (bounds_us * 1e-6) / 1e9, 1),
-        "roofline": {"kernel": "attn_mfma_kernel (split-K sparse paged attention)" if w.dtype == "bf16" else "attn_partials_generic_kernel", "bound": "hbm",
+        "roofline": {"kernel": "attn_mfma_kernel (split-K sparse paged attention; builds the union of the picked pages at start-up)" if w.dtype == "bf16" else "attn_partials_generic_kernel", "bound": "hbm",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "traffic_source": (f"profiles/traffic_{w.name}.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier "
+                                        "run of this workload, scaled by the calibration copy; not measured in this run)")
+                     if traffic is not None else None,
                      "frac_of_measured_copy": round(achieved / copy_gbps, 4) if copy_gbps else None,
+                     "frac_of_measured_scattered_read": round(achieved / read_gbps["scattered"], 4) if read_gbps else None,
                      "bytes_per_launch": int(attn_bytes), "us_per_launch": round(attn_us, 3)},
     }
 

@@ -277,6 +277,15 @@ losa_status losa_profile_read(losa_ctx* ctx, double* stage_ms, int64_t* stage_la
  * counters (FETCH_SIZE / WRITE_SIZE) are scaled by when the kernels above are profiled. */
 losa_status losa_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* A read-only stream kernel, enqueued on `stream`: 256 workgroups of four wavefronts read `num_tiles`
+ * tiles of `tile_bytes` bytes (a multiple of 16, at most 1 MiB) at pool + tile_ids[t] * tile_bytes, four
+ * tiles in flight per wavefront, and write nothing (`sink`, 4 KiB of device memory, 16-byte aligned, is
+ * only a formal destination).  The caller guarantees that every id addresses a tile inside the pool.  It
+ * gives the read rate this GPU reaches on tiles of the page size, in order or scattered, which is
+ * what the attention kernel's achieved bandwidth is set against beside the 8 TB/s peak. */
+losa_status losa_calibration_read(const void* pool, size_t tile_bytes, const int32_t* tile_ids, int32_t num_tiles,
+                                  void* sink, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ LOSA_SEL_TOPK, LOSA_SEL_FRACTION, LOSA_SEL_THRESHOLD, LOSA_SEL_MASS = 0, 1, 2, 3
 EXPORTS = ["losa_workspace_bytes", "losa_create", "losa_destroy", "losa_last_error", "losa_select_active",
            "losa_page_bounds", "losa_score_pages", "losa_sparse_attn", "losa_step", "losa_profile_enable",
            "losa_profile_read", "losa_calibration_copy", "losa_block_merge", "losa_score_pages_shared",
-           "losa_select_active_static", "losa_set_tuning"]
+           "losa_select_active_static", "losa_set_tuning", "losa_calibration_read"]
 (LOSA_TUNE_ATTN_WORKGROUPS, LOSA_TUNE_SELECT_ROUND, LOSA_TUNE_SCORE_ROUND, LOSA_TUNE_RANK_IN_SCORES,
  LOSA_TUNE_UNION_IN_ATTENTION, LOSA_TUNE_SHARED_TILES) = range(6)
 STAGES = ["locality", "score", "topk", "attn", "merge", "bounds", "block"]
@@ -89,6 +89,8 @@ def load_library() -> C.CDLL:
     lib.losa_block_merge.argtypes = [vp, vp, i32, p, p, p, p, p, p, p, p]
     lib.losa_calibration_copy.restype = C.c_int
     lib.losa_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    lib.losa_calibration_read.restype = C.c_int
+    lib.losa_calibration_read.argtypes = [vp, C.c_size_t, vp, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -247,6 +249,12 @@ def losa_calibration_copy(dst, src, stream=None):
     """Plain copy of src into dst (same byte size): the known-size reference for byte counters."""
     nbytes = src.numel() * src.element_size()
     _check(None, load_library().losa_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))
+
+
+def losa_calibration_read(pool, tile_bytes: int, tile_ids, sink, stream=None):
+    """Read-only stream over the tiles of `pool` listed in tile_ids (int32 tensor); nothing is written."""
+    _check(None, load_library().losa_calibration_read(_ptr(pool), tile_bytes, _ptr(tile_ids), int(tile_ids.numel()),
+                                                     _ptr(sink), _stream(stream)))
 
 
 def losa_block_merge(ctx: Context, q, k_b, v_b, o_p, lse_p, out, o_b=None, lse_b=None, batch: Optional[int] = None,

@@ -3,11 +3,16 @@ profiles/.
 
     python -m paper_2604_12056_amd.profile_summary trace  <dir-with-*_kernel_trace.csv>
     python -m paper_2604_12056_amd.profile_summary traffic <fetch-dir> <write-dir> --copy-bytes N
+    python -m paper_2604_12056_amd.profile_summary counters <dir> [<dir> ...]
 
 `trace` prints calls / mean / min / max duration per kernel.  `traffic` reads two counter
 runs (FETCH_SIZE in one, WRITE_SIZE in the other; KiB per dispatch), scales each counter by
 what it reads for the library's calibration copy kernel of known size, and prints HBM bytes
-per launch for every kernel of the library, in the key: value form bench.py reads back."""
+per launch for every kernel of the library, in the key: value form bench.py reads back.
+`counters` prints, for every kernel of the library, the mean per launch of every counter found
+in the given counter runs (one table row per kernel and run), plus the derived figures the
+matrix-core kernels are judged by: matrix-core busy, vector-ALU busy and both-at-once cycles as
+fractions of the kernel's busy cycles."""
 from __future__ import annotations
 
 import argparse
@@ -75,6 +80,39 @@ def traffic(fetch_dir: str, write_dir: str, copy_bytes: int) -> None:
             break
 
 
+def counters(dirs) -> None:
+    """Mean counter values per launch.  The SQ_* cycle counters count per SIMD (MFMA busy, co-execution)
+    or per wavefront in units of four cycles (ACTIVE_INST_*, WAVE_CYCLES, WAIT_*), BUSY_CU_CYCLES per
+    compute unit; the derived fractions put each on the kernel's own duration in cycles."""
+    for d in dirs:
+        rows = csv.DictReader(open(_find(d, "_counter_collection.csv")))
+        acc = collections.defaultdict(lambda: collections.defaultdict(list))
+        for r in rows:
+            acc[_short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        names = sorted({c for v in acc.values() for c in v})
+        print(f"# counter run {os.path.basename(os.path.normpath(d))}: " + " ".join(names))
+        for k in sorted(acc):
+            if "losa::" not in k:
+                continue
+            v = {c: sum(x) / len(x) for c, x in acc[k].items()}
+            n = len(next(iter(acc[k].values())))
+            print(f"{k[:84]:84s} launches {n}")
+            for c in names:
+                if c in v:
+                    print(f"    {c:34s} {v[c]:18.1f}")
+            cu = v.get("SQ_BUSY_CU_CYCLES")
+            if cu:
+                # 256 compute units x 4 SIMDs; a kernel that keeps every unit busy for its whole duration has
+                # BUSY_CU_CYCLES = 256 x duration in cycles
+                dur = cu / 256.0
+                if "SQ_VALU_MFMA_BUSY_CYCLES" in v:
+                    print(f"    {'matrix-core busy / duration':34s} {v['SQ_VALU_MFMA_BUSY_CYCLES'] / 1024.0 / dur:18.3f}")
+                if "SQ_VALU_MFMA_COEXEC_CYCLES" in v:
+                    print(f"    {'matrix + vector at once / duration':34s} {v['SQ_VALU_MFMA_COEXEC_CYCLES'] / 1024.0 / dur:18.3f}")
+                if "SQ_ACTIVE_INST_VALU" in v:
+                    print(f"    {'vector-ALU issue busy / duration':34s} {v['SQ_ACTIVE_INST_VALU'] * 4.0 / 1024.0 / dur:18.3f}")
+
+
 def main(argv=None) -> None:
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -84,9 +122,13 @@ def main(argv=None) -> None:
     f.add_argument("fetch_dir")
     f.add_argument("write_dir")
     f.add_argument("--copy-bytes", type=int, required=True)
+    c = sub.add_parser("counters")
+    c.add_argument("dirs", nargs="+")
     a = ap.parse_args(argv)
     if a.cmd == "trace":
         trace(a.dir)
+    elif a.cmd == "counters":
+        counters(a.dirs)
     else:
         traffic(a.fetch_dir, a.write_dir, a.copy_bytes)
 

@@ -34,3 +34,24 @@ def test_traffic_picks_the_split_pages_kernel_and_scales_by_the_copy(tmp_path):
     # kernel, whose name also carries a "true", is not the one reported
     assert float(vals["attn_fetch_bytes_per_launch"]) == 200.0 * 1024 * 2.0
     assert float(vals["attn_write_bytes_per_launch"]) == 20.0 * 1024 * 1.0
+
+
+def test_counters_reports_means_and_busy_fractions(tmp_path):
+    """A kernel that keeps all 256 compute units busy for 1000 cycles, its matrix cores for 400 of
+    them on every one of the 1024 SIMDs and its vector ALUs for 150 four-cycle issue slots."""
+    d = str(tmp_path / "run")
+    os.makedirs(d)
+    with open(os.path.join(d, "p_counter_collection.csv"), "w", newline="") as f:
+        w = csv.DictWriter(f, fieldnames=["Kernel_Name", "Counter_Name", "Counter_Value"])
+        w.writeheader()
+        for name, vals in (("SQ_BUSY_CU_CYCLES", [256e3, 256e3]), ("SQ_VALU_MFMA_BUSY_CYCLES", [400.0 * 1024] * 2),
+                           ("SQ_ACTIVE_INST_VALU", [150.0 * 1024, 150.0 * 1024])):
+            for v in vals:
+                w.writerow({"Kernel_Name": MANY_ROWS, "Counter_Name": name, "Counter_Value": v})
+    r = subprocess.run([sys.executable, "-m", "paper_2604_12056_amd.profile_summary", "counters", d], capture_output=True,
+                       text=True, cwd=ROOT)
+    assert r.returncode == 0, r.stderr
+    lines = {" ".join(l.split()[:-1]): l.split()[-1] for l in r.stdout.splitlines() if l.startswith("    ")}
+    assert float(lines["matrix-core busy / duration"]) == 0.4
+    assert float(lines["vector-ALU issue busy / duration"]) == 0.6
+    assert "launches 2" in r.stdout
