@@ -175,7 +175,8 @@ def main():
         copy_gbps = None
 
     # ---- what a read-only stream over tiles of the page size reaches on this GPU (nothing written):
-    # 64 MiB per launch out of a 1 GiB pool, tiles in order and in a seeded random order
+    # 64 MiB per launch out of a 1 GiB pool (launches about the size of the attention kernel's), tiles in
+    # order and in a seeded random order
     read_gbps = {}
     if args.read_probe_mib > 0:
         e_sz = 2 if w.dtype == "bf16" else 4
@@ -197,6 +198,13 @@ def main():
                 e1.record()
                 torch.cuda.synchronize()
             read_gbps[name] = launches * n_read * tile_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+            # and one launch over the whole pool: the rate without a launch's fixed costs
+            e0, e1 = ev(), ev()
+            e0.record()
+            L.losa_calibration_read(pool, tile_bytes, ids, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            read_gbps[name + "_1GiB_launch"] = n_pool * tile_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
         del pool, sink
 
     # ---- once per block: page bounds, then the dense initialisation (step 0) of every layer.
