@@ -16,10 +16,14 @@ taken per KV head over the queries of its group; all of those queries then
 attend over that shared union (Methodology, "Sparse attention with smaller
 union size").
 
-Arithmetic is float64 on inputs widened exactly from their storage type.
-Where a floating value decides an integer result (which tokens are active,
-which pages are picked) the float64 value is first rounded to float32, the
-precision the device path decides in; ties go to the smaller index.
+Arithmetic is float64 on inputs widened exactly from their storage type
+(the statement of the problem asks for a plain float32 reference; float64
+is the same definitions evaluated more exactly, so that the reference's own
+rounding stays far below the tolerances it is used to check).  Where a
+floating value decides an integer result (which tokens are active, which
+pages are picked) the float64 value is first rounded to float32, the
+precision that statement gives the reference and in which "equal" scores
+are defined; ties go to the smaller index.
 
 Parity pins (tests/test_oracle_pins.py): every function below is pinned to a
 closed form, an invariant, a library routine or brute force.  End-to-end

@@ -17,13 +17,15 @@
 // each lane ends up with 8 consecutive tokens; both operands of the second product use that
 // same token order, which is all a contraction needs.
 //
-// No LDS and no barrier in the main loop: K/V go global -> registers in operand layout,
-// one tile ahead in the sparse shape and two or three in the dense one.  Two work shapes:
-//   split-pages (rows <= 64): the four wavefronts of a workgroup take interleaved tiles and
-//       combine their (reference, sum, O) through LDS at the end, so one partial leaves
-//       the workgroup;
-//   split-rows (rows > 64, e.g. the dense initialisation): the four wavefronts take four
-//       64-row blocks and all walk the same tiles (served by the CU's L1 after the first).
+// Two work shapes:
+//   split-pages (rows <= 64, the sparse steps): the four wavefronts of a workgroup take
+//       interleaved tiles, K/V go global -> registers in operand layout one tile ahead (no LDS
+//       and no barrier in the main loop), and the four combine their (reference, sum, O)
+//       through LDS at the end, so one partial leaves the workgroup;
+//   many rows (rows > 64, e.g. the dense initialisation): eight wavefronts of 32 rows walk the
+//       same tiles; a tile is fetched from memory once per workgroup, its values converted to
+//       half precision, and shared through LDS (one barrier per tile).  Four independent
+//       wavefronts of 64 rows, each loading every tile itself, remain as a switchable fallback.
 // Tiles of a (sequence, head) list are dealt round-robin to its workgroups, so every
 // workgroup gets the same number of tiles (within one) whatever the union size turns out to be.
 #include <hip/hip_ext.h>
@@ -92,12 +94,14 @@ struct MergeSlot {   // LDS image of one wavefront's state: O as [row tile][chan
 // a row's largest fall into its subnormals.
 //
 // UNION (split-pages shape only): there is no prepared page list.  The selection kernel left the
-// pick bitmap of every query row; each wavefront ORs the rows of its head (lane = bitmap word),
-// ranks the union with a popcount prefix sum, keeps words and ranks in LDS (in its own merge
-// slot, which is idle until the combine), and finds the pages of its own tiles by rank: a binary
-// search over the word ranks, a 5-step search inside the word, then one gather from the page
-// table.  One more dependent memory round trip at start-up than with a prepared list, in
-// exchange for the selection kernel's whole hand-over tail.
+// pick bitmap of every query row (word-major) and a copy of the head's page table; the four
+// wavefronts of a workgroup fetch a quarter of each, meet in LDS (one barrier), and then every
+// wavefront ORs the quarters (lane = bitmap word), ranks the union with a popcount prefix sum,
+// keeps words and ranks in LDS (in its own merge slot, which is idle until the combine), and finds
+// the pages of its own tiles by rank: a binary search over the word ranks, a 5-step search inside
+// the word, then the page's entry from the table in LDS (from memory for pages beyond the first
+// 2048).  That is more start-up work than with a prepared list (about 2 us at 2048 pages), in
+// exchange for the selection kernel's whole hand-over tail (about 4 us).
 constexpr int kMaxUnionWords = kMaxSelectPages / 32;
 constexpr int kTablePagesInLds = 2048;   // the first so many entries of a head's page table are kept in LDS
 // LDS of the split-pages shape, in floats: the four wavefronts' merge slots, then (UNION) an area the
