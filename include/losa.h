@@ -196,7 +196,11 @@ losa_status losa_score_pages_shared(losa_ctx* ctx, void* stream, const losa_kv* 
  *   sel_pages, sel_count     : both NULL = every page (dense prefix attention)
  *   o_p   : float [batch*B, Hq, d]  in/out
  *   lse_p : float [batch*B, Hq]     in/out (natural log)
- * A sequence with no selected token gives o_p = 0, lse_p = -inf for its active rows. */
+ * A sequence with no selected token gives o_p = 0, lse_p = -inf for its active rows.
+ * Accuracy against exact attention of the given inputs: bfloat16 mode max-abs 2e-2 for values of
+ * ordinary activation size (products accumulate in float; probabilities enter the value product
+ * with 16 significant bits for up to 64 query rows per KV head, with 11 beyond that - see
+ * LOSA_TUNE_HALF_PRECISION_VALUES, which also bounds |v| by 65504 there); float mode 1e-4. */
 losa_status losa_sparse_attn(losa_ctx* ctx, void* stream, const losa_kv* kv, const void* q,
                              const int32_t* active_idx, const int32_t* active_count,
                              const int32_t* sel_pages, const int32_t* sel_count, int32_t cap,
@@ -226,8 +230,11 @@ losa_status losa_block_merge(losa_ctx* ctx, void* stream, int32_t batch, const v
                              const void* v_b, const float* o_p, const float* lse_p, float* out, float* o_b,
                              float* lse_b);
 
-/* Tuning switches of a context: how the launches are shaped, never what they compute (results are
- * bit-identical for every setting).  Each has a default chosen by measurement on MI355X; tests
+/* Tuning switches of a context: how the launches are shaped, never what they compute: every
+ * decision (active set, picked pages, unions) is the same for every setting, and so is every
+ * output bit except under the last two switches, which change the rounding order of the attention
+ * over more than 64 query rows per KV head (outputs stay inside the bounds stated for losa_sparse_attn).
+ * Each has a default chosen by measurement on MI355X; tests
  * use them to drive the code paths a workload of their size would not reach.  A value takes
  * effect with the next call on the context.
  *   LOSA_TUNE_ATTN_WORKGROUPS   : attention workgroups aimed at per launch (default 256: one per
@@ -241,14 +248,22 @@ losa_status losa_block_merge(losa_ctx* ctx, void* stream, int32_t batch, const v
  *                                 row count known to the host build the union of the picked pages in the
  *                                 attention kernel; 0: in the selection kernel, as in losa_score_pages
  *   LOSA_TUNE_SHARED_TILES      : 1 (default): above 64 query rows per KV head eight wavefronts share
- *                                 each key/value tile through LDS; 0: four independent wavefronts */
+ *                                 each key/value tile through LDS; 0: four independent wavefronts
+ *   LOSA_TUNE_HALF_PRECISION_VALUES: 1 (default): in that shared-tile form the value product runs in
+ *                                 half precision: probabilities rounded once to 11 significant bits
+ *                                 (output error up to 2^-10 of the largest |v| a row attends to, in
+ *                                 practice a tenth of that), values converted bfloat16 -> half, which
+ *                                 is exact up to |v| = 65504 and saturates there; 0: probabilities as
+ *                                 a bfloat16 pair (2^-16) and values in bfloat16's own range, at about
+ *                                 a fifth more time.  Steps with up to 64 rows always take the pair. */
 typedef enum {
   LOSA_TUNE_ATTN_WORKGROUPS = 0,
   LOSA_TUNE_SELECT_ROUND = 1,
   LOSA_TUNE_SCORE_ROUND = 2,
   LOSA_TUNE_RANK_IN_SCORES = 3,
   LOSA_TUNE_UNION_IN_ATTENTION = 4,
-  LOSA_TUNE_SHARED_TILES = 5
+  LOSA_TUNE_SHARED_TILES = 5,
+  LOSA_TUNE_HALF_PRECISION_VALUES = 6
 } losa_tuning;
 losa_status losa_set_tuning(losa_ctx* ctx, losa_tuning knob, int64_t value);
 

@@ -21,7 +21,7 @@ EXPORTS = ["losa_workspace_bytes", "losa_create", "losa_destroy", "losa_last_err
            "losa_profile_read", "losa_calibration_copy", "losa_block_merge", "losa_score_pages_shared",
            "losa_select_active_static", "losa_set_tuning", "losa_calibration_read"]
 (LOSA_TUNE_ATTN_WORKGROUPS, LOSA_TUNE_SELECT_ROUND, LOSA_TUNE_SCORE_ROUND, LOSA_TUNE_RANK_IN_SCORES,
- LOSA_TUNE_UNION_IN_ATTENTION, LOSA_TUNE_SHARED_TILES) = range(6)
+ LOSA_TUNE_UNION_IN_ATTENTION, LOSA_TUNE_SHARED_TILES, LOSA_TUNE_HALF_PRECISION_VALUES) = range(7)
 STAGES = ["locality", "score", "topk", "attn", "merge", "bounds", "block"]
 
 

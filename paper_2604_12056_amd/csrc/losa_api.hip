@@ -81,6 +81,7 @@ struct losa_ctx {
   bool rank_in_scores;      // losa_step lets the scoring kernel rank the locality scores
   bool union_in_attention;  // sparse steps of up to 64 rows: the attention kernel builds the union
   bool shared_tiles;        // more than 64 rows: 8 wavefronts share each tile through LDS (else 4 independent ones)
+  bool half_values;         // ... and their value product runs in half precision (else P as a bfloat16 pair)
   AttnPrepared prep;
   char err[256];
   // measurement hooks
@@ -373,15 +374,17 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
   }
   {
     StageTimer timer(ctx, st, LOSA_STAGE_ATTN, /*bind_to_dispatch=*/mfma && !both_shapes);
+    const int many_rows = !ctx->shared_tiles ? kManyRowsIndependent
+                                             : (ctx->half_values ? kManyRowsSharedHalf : kManyRowsSharedPair);
     if (both_shapes) {
       e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, 64, part, nullptr, nullptr, 0, 64, nullptr,
-                           ctx->shared_tiles);
+                           many_rows);
       if (e == hipSuccess)
         e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, ctx->sh.rows_max, part, nullptr, nullptr,
-                             64, 0x7fffffff, nullptr, ctx->shared_tiles);
+                             64, 0x7fffffff, nullptr, many_rows);
     } else if (mfma)
       e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, rows_upper, part, timer.start(),
-                           timer.stop(), 0, 0x7fffffff, uni, ctx->shared_tiles);
+                           timer.stop(), 0, 0x7fffffff, uni, many_rows);
     else
       e = launch_attn_generic(st, ctx->cfg.dtype, kv, ctx->sh, batch, q, active_idx, active_count, sel_pages,
                               sel_count, cap, nchunk, part);
@@ -450,6 +453,7 @@ losa_status losa_create(const losa_config* cfg, void* workspace, size_t workspac
   ctx->score_round = 5L * 256;   // about five scoring workgroups per CU are resident at once
   ctx->union_in_attention = true;
   ctx->shared_tiles = true;
+  ctx->half_values = true;
   ctx->prep.entries = (int32_t*)(base + L.entries);
   ctx->prep.q_act = (uint16_t*)(base + L.q_act);
   ctx->prep.ucount = (int32_t*)(base + L.ucount);
@@ -485,6 +489,7 @@ losa_status losa_set_tuning(losa_ctx* ctx, losa_tuning knob, int64_t value) {
     case LOSA_TUNE_RANK_IN_SCORES: ctx->rank_in_scores = value != 0; return LOSA_OK;
     case LOSA_TUNE_UNION_IN_ATTENTION: ctx->union_in_attention = value != 0; return LOSA_OK;
     case LOSA_TUNE_SHARED_TILES: ctx->shared_tiles = value != 0; return LOSA_OK;
+    case LOSA_TUNE_HALF_PRECISION_VALUES: ctx->half_values = value != 0; return LOSA_OK;
   }
   return fail(ctx, LOSA_ERR_INVALID_ARG, "unknown tuning switch %d", (int)knob);
 }

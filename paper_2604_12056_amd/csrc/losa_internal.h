@@ -123,11 +123,17 @@ hipError_t launch_attn_generic(hipStream_t st, int dtype, const KvView& kv, cons
 hipError_t launch_attn_prepare(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const void* q,
                                const int32_t* active_idx, const int32_t* active_count, const int32_t* sel_pages,
                                const int32_t* sel_count, int cap, const AttnPrepared& prep);
+// The attention kernel's form above 64 query rows per KV head.
+enum ManyRowForm : int {
+  kManyRowsIndependent = 0,   // 4 wavefronts of 64 rows, each loading every tile itself; P as a bfloat16 pair
+  kManyRowsSharedHalf = 1,    // 8 wavefronts of 32 rows, tiles shared through LDS, value product in half precision
+  kManyRowsSharedPair = 2     // the same sharing, P as a bfloat16 pair (values keep bfloat16's range)
+};
 // e0/e1 (both or neither): events bound to the dispatch itself, for exact kernel timing.
 hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                             int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1,
                             int m_lo = 0, int m_hi = 0x7fffffff,   // serves (sequence, head) pairs with m_lo < rows <= m_hi
-                            const UnionInKernel* uni = nullptr, bool shared_tiles = true);
+                            const UnionInKernel* uni = nullptr, int many_rows = kManyRowsSharedHalf);
 hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, int batch,
                              const int32_t* active_idx, const int32_t* active_count,
                              const int32_t* sel_count, int cap, int nchunk, const AttnPrepared* prep,

@@ -931,12 +931,12 @@ static hipError_t launch_one(hipStream_t st, const KvView& kv, const Shape& sh, 
   return hipGetLastError();
 }
 
-// Many rows: 8 wavefronts of 32 rows sharing tiles through LDS, or (shared_tiles off) 4 independent
-// wavefronts of 64 rows.
+// Many rows (many_rows: ManyRowForm): 8 wavefronts of 32 rows sharing tiles through LDS, with the value
+// product in half precision or as a bfloat16 pair, or 4 independent wavefronts of 64 rows.
 template <int D, int GP>
 static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                             int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1, int m_lo,
-                            int m_hi, const UnionInKernel* uni, bool shared_tiles) {
+                            int m_hi, const UnionInKernel* uni, int many_rows) {
   if (uni && uni->rowmaps) {   // the kernel builds the union from the row bitmaps itself
     if (rows_upper <= 16) return launch_one<D, GP, 1, true, 4, false, false, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi, *uni);
     if (rows_upper <= 32) return launch_one<D, GP, 2, true, 4, false, false, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi, *uni);
@@ -951,21 +951,23 @@ static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, i
   // (16 rows per wavefront for up to 128 rows, so that all 8 wavefronts have work, was measured
   // and is slower than 4 busy wavefronts of 32 rows: every wavefront reads the whole tile from
   // LDS whatever its row count, so halving the rows halves the reuse of each operand read.)
-  if (shared_tiles)
+  if (many_rows == kManyRowsSharedHalf)
     return launch_one<D, GP, 2, false, 8, true, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
+  if (many_rows == kManyRowsSharedPair)
+    return launch_one<D, GP, 2, false, 8, true, false>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
   return launch_one<D, GP, 4, false>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi);
 }
 
 hipError_t launch_attn_mfma(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                             int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1, int m_lo,
-                            int m_hi, const UnionInKernel* uni, bool shared_tiles) {
+                            int m_hi, const UnionInKernel* uni, int many_rows) {
   if (batch <= 0 || nchunk <= 0) return hipSuccess;
   if (sh.d == 128) {
-    if (sh.g == 16) return launch_dg<128, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni, shared_tiles);
-    return launch_dg<128, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni, shared_tiles);
+    if (sh.g == 16) return launch_dg<128, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni, many_rows);
+    return launch_dg<128, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni, many_rows);
   }
-  if (sh.g == 16) return launch_dg<64, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni, shared_tiles);
-  return launch_dg<64, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni, shared_tiles);
+  if (sh.g == 16) return launch_dg<64, 16>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni, many_rows);
+  return launch_dg<64, 32>(st, kv, sh, batch, prep, nchunk, rows_upper, part, e0, e1, m_lo, m_hi, uni, many_rows);
 }
 
 }  // namespace losa

@@ -112,6 +112,7 @@ def test_workspace_checks_and_argument_validation(lib):
         assert lib.losa_set_tuning(ctx, binding.LOSA_TUNE_SCORE_ROUND, 0) == inv
         assert lib.losa_set_tuning(ctx, 99, 1) == inv
         assert lib.losa_set_tuning(ctx, binding.LOSA_TUNE_SHARED_TILES, 0) == binding.LOSA_OK
+        assert lib.losa_set_tuning(ctx, binding.LOSA_TUNE_HALF_PRECISION_VALUES, 0) == binding.LOSA_OK
         assert lib.losa_set_tuning(None, binding.LOSA_TUNE_SHARED_TILES, 0) == inv
     finally:
         assert lib.losa_destroy(ctx) == binding.LOSA_OK

@@ -492,12 +492,15 @@ def test_pages_listed_beyond_the_tokens_are_ignored():
 
 
 @pytest.mark.parametrize("tuning", [{L.LOSA_TUNE_UNION_IN_ATTENTION: 0}, {L.LOSA_TUNE_SHARED_TILES: 0},
+                                    {L.LOSA_TUNE_HALF_PRECISION_VALUES: 0},
                                     {L.LOSA_TUNE_ATTN_WORKGROUPS: 7}, {L.LOSA_TUNE_ATTN_WORKGROUPS: 1024}],
-                         ids=["union-in-selection", "independent-wavefronts", "7-workgroups", "1024-workgroups"])
+                         ids=["union-in-selection", "independent-wavefronts", "bfloat16-pair-values", "7-workgroups",
+                              "1024-workgroups"])
 def test_launch_shape_switches_do_not_change_results(tuning):
     """Every tuning switch of a context selects another launch shape for the same computation:
     the union built by the selection kernel instead of the attention kernel, four independent
-    wavefronts instead of eight sharing tiles, other numbers of attention workgroups.  Each setting
+    wavefronts instead of eight sharing tiles, the shared-tile value product with probabilities as a
+    bfloat16 pair instead of half precision, other numbers of attention workgroups.  Each setting
     against the oracle, on a sparse-step shape, a many-row shape and a ragged batch."""
     many = synth.config(0).replace(B=64, Hq=32, Hkv=4, d=128, g=16, n_active=40, batch=2, seq_lens=(1900, 777),
                                    topk_pages=6, T=3, name="many-rows")
