@@ -79,6 +79,14 @@ def test_c1_full_float_mode():
     _run(synth.config(1, dtype="f32").replace(T=2, seq_lens=(8192 + 40,)), range(2))
 
 
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_float_mode_at_the_stated_sizes(cfg):
+    """The float validation mode at each benchmark configuration's own size (C1 32k, C2 sixteen
+    ragged sequences, C3 128k, C4 four sequences of 64k with 64-token blocks and 32-token pages):
+    dense initialisation and a sparse step, every decision and output against the oracle at 1e-4."""
+    _run(synth.config(cfg, dtype="f32").replace(T=2), range(2))
+
+
 @pytest.mark.parametrize("pages,tail", [(3001, 5), (9001, 5), (9004, 11), (16384, 0)])
 def test_long_sequences_up_to_the_page_limit(pages, tail):
     """Above 2048 / 8192 pages the selection kernel holds 32 / 64 keys per thread (16384 pages is
