@@ -151,7 +151,6 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
       pg_entry = lp < sh.max_pages ? ent[lp] : 0;   // inside the array whatever U is; checked against U at use
     }
   };
-  // UNION: words and ranks of the head's union, in this wavefront's own merge slot
   // UNION: words and ranks of the head's union, in this wavefront's own merge slot; the page table and
   // the staging of the OR in the area behind the slots
   [[maybe_unused]] uint32_t* u_bits = reinterpret_cast<uint32_t*>(lds + (SPLIT_PAGES ? wave : 0) * kSlotStride);
@@ -181,16 +180,30 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
     // head's row count were cleared by the selection kernel), so a lane ORs its word over rows with
     // 16-byte loads at constant offsets: one memory latency, no per-row addressing
     const uint32_t* maps = uni.rowmaps + (size_t)head * words * kUnionRows;
-    for (int g0 = 0; g0 < words; g0 += 64) {
-      const int w = g0 + lane;
-      const u32x4v_t* col = reinterpret_cast<const u32x4v_t*>(maps + (size_t)min(w, words - 1) * kUnionRows) + wave * R;
-      u32x4v_t v[R];
+    // (the loads of up to four groups of 64 words are issued before the first is used: taken one
+    // group at a time, each group costs a memory round trip of its own - 8192 pages are four groups)
+    constexpr int kGroupsInFlight = 4;
+    for (int g0 = 0; g0 < words; g0 += 64 * kGroupsInFlight) {
+      u32x4v_t v[kGroupsInFlight][R];
 #pragma unroll
-      for (int k = 0; k < R; ++k) v[k] = col[k];   // this wavefront's quarter of the R * 16 row slots
-      uint32_t acc = 0u;
+      for (int u = 0; u < kGroupsInFlight; ++u) {
+        if (g0 + 64 * u < words) {   // uniform over the workgroup
+          const int w = g0 + 64 * u + lane;
+          const u32x4v_t* col = reinterpret_cast<const u32x4v_t*>(maps + (size_t)min(w, words - 1) * kUnionRows) + wave * R;
 #pragma unroll
-      for (int k = 0; k < R; ++k) acc |= (v[k][0] | v[k][1]) | (v[k][2] | v[k][3]);
-      u_stage[wave * kMaxUnionWords + w] = acc;   // w < kMaxUnionWords: max_pages <= 32 * kMaxUnionWords
+          for (int k = 0; k < R; ++k) v[u][k] = col[k];   // this wavefront's quarter of the R * 16 row slots
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kGroupsInFlight; ++u) {
+        if (g0 + 64 * u < words) {
+          const int w = g0 + 64 * u + lane;
+          uint32_t acc = 0u;
+#pragma unroll
+          for (int k = 0; k < R; ++k) acc |= (v[u][k][0] | v[u][k][1]) | (v[u][k][2] | v[u][k][3]);
+          if (w < words) u_stage[wave * kMaxUnionWords + w] = acc;   // words <= kMaxUnionWords: max_pages <= 32 * kMaxUnionWords
+        }
+      }
     }
 #pragma unroll
     for (int k = 0; k < TPW; ++k) reinterpret_cast<u32x4v_t*>(u_tab)[wave * (64 * TPW) + lane + 64 * k] = tabv[k];
