@@ -244,9 +244,9 @@ losa_status losa_block_merge(losa_ctx* ctx, void* stream, int32_t batch, const v
  *   LOSA_TUNE_SCORE_ROUND       : the same for the scoring kernel (64-page tiles per workgroup); >= 1
  *   LOSA_TUNE_RANK_IN_SCORES    : 1 (default): inside losa_step the scoring kernel ranks the locality
  *                                 scores itself; 0: the locality kernel does, as in losa_select_active
- *   LOSA_TUNE_UNION_IN_ATTENTION: 1 (default): sparse steps with up to 64 query rows per KV head and a
- *                                 row count known to the host build the union of the picked pages in the
- *                                 attention kernel; 0: in the selection kernel, as in losa_score_pages
+ *   LOSA_TUNE_UNION_IN_ATTENTION: 1 (default): (sequence, KV head) pairs with up to 64 active query rows
+ *                                 have the union of their picked pages built in the attention kernel;
+ *                                 0: in the selection kernel, as in losa_score_pages
  *   LOSA_TUNE_SHARED_TILES      : 1 (default): above 64 query rows per KV head eight wavefronts share
  *                                 each key/value tile through LDS; 0: four independent wavefronts
  *   LOSA_TUNE_HALF_PRECISION_VALUES: 1 (default): in that shared-tile form the value product runs in

@@ -377,7 +377,7 @@ losa_status sparse_attn_impl(losa_ctx* ctx, hipStream_t st, const KvView& kv, in
     const int many_rows = !ctx->shared_tiles ? kManyRowsIndependent
                                              : (ctx->half_values ? kManyRowsSharedHalf : kManyRowsSharedPair);
     if (both_shapes) {
-      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, 64, part, nullptr, nullptr, 0, 64, nullptr,
+      e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, 64, part, nullptr, nullptr, 0, 64, uni,
                            many_rows);
       if (e == hipSuccess)
         e = launch_attn_mfma(st, kv, ctx->sh, batch, ctx->prep, nchunk, ctx->sh.rows_max, part, nullptr, nullptr,
@@ -707,10 +707,15 @@ losa_status losa_step(losa_ctx* ctx, void* stream, const losa_kv* kv, int32_t st
   // the host knows |A| in the top-n modes, so selection and attention can be shaped for n*G rows
   const bool counted = mode == LOSA_SEL_TOPK || mode == LOSA_SEL_FRACTION;
   const int rows_upper = counted ? select_count(ctx, (int)mode, param) * ctx->sh.G : 0;
-  // Up to 64 query rows per KV head and a row count the host knows: the attention workgroups build
-  // the union of the per-row picks themselves, and the selection kernel ends with the row bitmaps.
-  const bool union_in_attn = fuse_prepare && counted && rows_upper >= 1 && rows_upper <= 64 && ctx->union_in_attention;
-  const UnionInKernel uni{ctx->rowmaps, sc};
+  // Up to 64 query rows per KV head: the attention workgroups build the union of the per-row picks
+  // themselves, and the selection kernel ends with the row bitmaps.  With a count only the device
+  // knows, the selection kernel does so for the heads it finds with at most 64 rows, and the attention
+  // launch for those heads takes their row-tile counts from the device; heads with more rows get the
+  // union list and the many-row launch as before.
+  const bool union_counted = fuse_prepare && counted && rows_upper >= 1 && rows_upper <= 64 && ctx->union_in_attention;
+  const bool union_on_device = fuse_prepare && !counted && ctx->sh.rows_max <= 256 && ctx->union_in_attention;
+  const bool union_in_attn = union_counted || union_on_device;
+  const UnionInKernel uni{ctx->rowmaps, sc, union_on_device};
   s = score_pages_impl(ctx, st, view, kv->batch, msp, q, ctx->active_idx, ctx->active_count, topk_pages, nullptr,
                        ctx->sel_pages, sc, cap, fuse_prepare, rows_upper, rank_in_scores ? &ranking : nullptr,
                        union_in_attn);

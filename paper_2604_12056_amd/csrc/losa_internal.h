@@ -55,16 +55,26 @@ struct AttnPrepared {
   int32_t* mrows;     // [heads] query rows (|A| * G)
 };
 // The other way the matrix-core kernel can get its page list (sparse steps of losa_step with at
-// most 64 query rows per KV head and a row count the host knows): the selection kernel leaves
-// only the per-row pick bitmaps, and every attention workgroup ORs them, ranks the union and
-// resolves its own pages itself while it starts up.  That takes the selection kernel's serial
-// tail (bitmap hand-over to one workgroup per head, union, list) out of the chain of launches.
+// most 64 query rows per KV head): the selection kernel leaves only the per-row pick bitmaps, and
+// every attention workgroup ORs them, ranks the union and resolves its own pages itself while it
+// starts up.  That takes the selection kernel's serial tail (bitmap hand-over to one workgroup per
+// head, union, list) out of the chain of launches.  When the host does not know the row count
+// (threshold / cumulative-mass selection) the selection kernel decides per (sequence, KV head),
+// by the count it finds, which of the two forms it leaves, and the attention launch takes each
+// head's row-tile count from the device (rows_on_device).
 constexpr int kUnionRows = 64;   // row slots per bitmap word in that layout (the most rows the split-pages shape serves)
 struct UnionInKernel {
-  const uint32_t* rowmaps;   // [heads, words, kUnionRows] pick bitmaps, word-major: slot r of word w is row r's
-                             // word w, slots past the head's row count are zero; NULL: use AttnPrepared::entries
+  const uint32_t* rowmaps;   // [heads][words, kUnionRows] pick bitmaps, word-major: slot r of word w is row r's
+                             // word w, slots past the head's row count are zero; NULL: use AttnPrepared::entries.
+                             // A head's region is union_region_words() wide (it can hold the row-major form too).
   int32_t* sel_count;        // [heads] out: pages in the union (written by the head's first workgroup)
+  bool rows_on_device;       // host side only: launch the form that sizes itself by AttnPrepared::mrows
 };
+// 32-bit words of one (sequence, KV head) region of the row-bitmap buffer: `words` per row, for the
+// larger of the block's row count and the word-major layout's 64 slots
+__host__ __device__ inline size_t union_region_words(int rows_max, int words) {
+  return (size_t)words * (size_t)(rows_max > kUnionRows ? rows_max : kUnionRows);
+}
 
 // ---- losa_api.hip
 // Sets `n` ints to zero with a small fill kernel (safe to record into a captured graph).

@@ -370,7 +370,7 @@ struct SelectOut {
   const void* q;        // query tensor (for the gather into prep.q_act)
   const int32_t* active_idx;
   bool rows_known;      // the grid has exactly one workgroup per existing row (+ the gather workgroup)
-  bool bitmaps_only;    // leave the row bitmaps to the attention kernel: no hand-over, no union, no list
+  bool bitmaps_only;    // heads with at most kUnionRows rows: leave the row bitmaps to the attention kernel (no hand-over, no union, no list)
 };
 
 // Inclusive suffix scan over 256 histogram buckets by one wavefront: lane l owns buckets
@@ -603,12 +603,12 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     // the dense buffer the attention kernel reads, off the path of the selection.  Indices are
     // clamped so that every load can be issued before the one it depends on has been checked.
     if (out.prep.entries == nullptr || M <= 0) return;
-    if (out.bitmaps_only) {
+    if (out.bitmaps_only && M <= kUnionRows) {
       // nobody builds the union here, who would otherwise publish the row count; and the row slots
       // past it are cleared, so that the attention kernel can OR all slots without looking at the count
       if (tid == 0) out.prep.mrows[head] = M;
       const int wds = (sh.max_pages + 31) / 32, spare = kUnionRows - min(M, kUnionRows);
-      uint32_t* slots = out.rowmaps + (size_t)head * wds * kUnionRows;
+      uint32_t* slots = out.rowmaps + (size_t)head * union_region_words(sh.rows_max, wds);
       for (int i = tid; i < wds * spare; i += NT) slots[(size_t)(i / spare) * kUnionRows + (kUnionRows - spare) + i % spare] = 0u;
       // ... and the head gets its page table in the form the attention kernel consumes (physical id
       // and valid-token count of every logical page), at an address that kernel knows when it starts
@@ -723,9 +723,9 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     // per-die L2 slices); ordering is "my stores have completed (wait count zero), then my
     // ticket".  A full agent-scope fence would also work but writes back and invalidates whole
     // L2 slices, once per workgroup.
-    uint32_t* myrow = out.rowmaps + ((size_t)head * sh.rows_max + r) * words;
-    if (out.bitmaps_only) {   // read by the next launch: ordinary stores, into the word-major layout
-      uint32_t* slots = out.rowmaps + (size_t)head * words * kUnionRows;
+    uint32_t* myrow = out.rowmaps + (size_t)head * union_region_words(sh.rows_max, words) + (size_t)r * words;
+    if (out.bitmaps_only && M <= kUnionRows) {   // read by the next launch: ordinary stores, into the word-major layout
+      uint32_t* slots = out.rowmaps + (size_t)head * union_region_words(sh.rows_max, words);
       if (r < kUnionRows)
         for (int w = tid; w < words; w += NT) slots[(size_t)w * kUnionRows + r] = w < WORDS ? rowbits[w] : 0u;
     } else {
@@ -740,7 +740,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
       if (tid < 256) rl.hist[tid] = 0u;
     }
   }
-  if (out.bitmaps_only) return;
+  if (out.bitmaps_only && M <= kUnionRows) return;
   const int rows_done = r_end - r_first;
   __builtin_amdgcn_s_waitcnt(0);
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
@@ -766,7 +766,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     for (int i = 0; i < E; ++i)   // (an empty sequence has no entry of its own in the page table)
       phys[i] = P > 0 ? kv.page_indices[base + min(tid + NT * i, P - 1)] : 0;
   }
-  const uint32_t* maps = out.rowmaps + (size_t)head * sh.rows_max * words;
+  const uint32_t* maps = out.rowmaps + (size_t)head * union_region_words(sh.rows_max, words);
   {
     // Thread t ORs bitmap word (t mod nw) of every `groups`-th row in registers, 16 independent
     // loads at a time (a loop of load-then-use would pay one memory latency per iteration),
@@ -986,7 +986,7 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
                                int32_t* sel_count, int cap, uint32_t* rowmaps, int32_t* tickets,
                                const AttnPrepared* prep, int rows_hint, long workgroups_per_round, bool bitmaps_only) {
   if (batch <= 0) return hipSuccess;
-  if (bitmaps_only && (!prep || rows_hint < 1 || topk_out)) return hipErrorInvalidValue;
+  if (bitmaps_only && (!prep || topk_out)) return hipErrorInvalidValue;
   SelectOut out;
   out.bitmaps_only = bitmaps_only;
   out.topk_out = topk_out;
@@ -1010,7 +1010,10 @@ hipError_t launch_select_pages(hipStream_t st, const KvView& kv, const Shape& sh
   // one round still beats two rows per workgroup: measured on 16 sequences of 36 rows x 4 heads)
   const long fit_one = workgroups_per_round > 0 ? workgroups_per_round : (small ? (bitmaps_only ? 10L : 7L) * 256 : 256L);
   const long fit_many = workgroups_per_round > 0 ? workgroups_per_round : (small ? 5L * 256 : 256L);
-  const long wgs = (long)(rows + 1) * sh.Hkv * batch;
+  // (a count the host does not know: the grid has a workgroup for every possible row, and those past
+  // the count leave at once; sized as if a quarter of the rows existed, so that a typical active set
+  // is not made to share workgroups for the sake of rows that are not there)
+  const long wgs = (long)(rows + 1) * sh.Hkv * batch / (out.rows_known ? 1 : 4);
   int rpw = wgs <= fit_one ? 1 : (int)((wgs + fit_many - 1) / fit_many);
   rpw = rpw < 1 ? 1 : (rpw > 4 ? 4 : rpw);
   dim3 grid((rows + rpw - 1) / rpw + 1, sh.Hkv, batch);   // + the query-gather workgroup

@@ -203,13 +203,22 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(KvView kv, Shape sh, co
                                                          const int32_t* __restrict__ sel_count, int cap, int nchunk,
                                                          const int32_t* __restrict__ ucount,
                                                          const int32_t* __restrict__ mrows, Partials part,
-                                                         float* __restrict__ o_p, float* __restrict__ lse_p) {
+                                                         float* __restrict__ o_p, float* __restrict__ lse_p,
+                                                         int rows_known) {
   typedef typename std::conditional<LOG2, float, double>::type Acc;
   constexpr int C4 = D / 4, CL = 256 / C4;
   __shared__ Acc red[CL][D];
   __shared__ Acc lred[CL];
   __shared__ float wmax[CL];
   const int r = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  // A grid sized without knowing the row count (threshold / cumulative-mass selection) has a
+  // workgroup for every possible row: those look at the count first and leave, instead of
+  // fetching partials nobody wrote (a block of 224 possible rows with 35 active ones would fetch
+  // six times what it needs).
+  if (!rows_known) {
+    const int M0 = mrows ? mrows[b * sh.Hkv + j] : (active_idx ? min(active_count[b], sh.B) : sh.B) * sh.G;
+    if (r >= M0) return;
+  }
   // The first KSPEC chunks of this thread are fetched before it is known how many chunks are
   // live (slots exist for all nchunk work items): together with the counts below this makes
   // the kernel one memory round trip deep instead of three.
@@ -346,16 +355,17 @@ hipError_t launch_attn_merge(hipStream_t st, const KvView& kv, const Shape& sh, 
   dim3 grid(rows_hint >= 1 && rows_hint < sh.rows_max ? rows_hint : sh.rows_max, sh.Hkv, batch);
   const int32_t* uc = prep ? prep->ucount : nullptr;
   const int32_t* mr = prep ? prep->mrows : nullptr;
+  const int known = rows_hint >= 1 || !active_idx;   // (no list of active tokens: every row exists)
   if (sh.d == 128) {
     if (prep)
-      attn_merge_kernel<128, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p);
+      attn_merge_kernel<128, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p, known);
     else
-      attn_merge_kernel<128, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p);
+      attn_merge_kernel<128, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p, known);
   } else {
     if (prep)
-      attn_merge_kernel<64, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p);
+      attn_merge_kernel<64, true><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p, known);
     else
-      attn_merge_kernel<64, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p);
+      attn_merge_kernel<64, false><<<grid, 256, 0, st>>>(kv, sh, active_idx, active_count, sel_count, cap, nchunk, uc, mr, part, o_p, lse_p, known);
   }
   return hipGetLastError();
 }

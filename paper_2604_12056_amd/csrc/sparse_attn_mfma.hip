@@ -109,9 +109,8 @@ constexpr int kTablePagesInLds = 2048;   // the first so many entries of a head'
 constexpr int kUnionShared = 4 * kMaxUnionWords + kTablePagesInLds;
 template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF, int NWAVE = 4, bool LDS_TILES = false, bool F16V = false,
           bool UNION = false>
-__global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv,
-                                                        Partials part, float scale_log2e, int m_lo, int m_hi,
-                                                        UnionInKernel uni) {
+__device__ __forceinline__ void attn_mfma_body(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv, Partials part,
+                                               float scale_log2e, int m_lo, int m_hi, UnionInKernel uni, float* lds) {
   static_assert(!UNION || SPLIT_PAGES, "the union is built in the kernel only in the split-pages shape");
   static_assert(!UNION || MergeSlot<D, R>::kFloats >= 2 * kMaxUnionWords, "the union's words and ranks do not fit a merge slot");
   constexpr int kSlotStride = MergeSlot<D, R>::kFloats;
@@ -119,7 +118,6 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   constexpr int NT = D / 16;    // channel tiles of the output
   constexpr int PPT = 32 / GP;  // pages per 32-token tile
   constexpr int TPR = 64 / PPT; // tiles covered by one page-entry fetch (one entry per lane)
-  extern __shared__ __attribute__((aligned(16))) float lds[];
 
   // the wavefront number is the same for all lanes; saying so keeps what derives from it (tile
   // numbers, loop bounds, page ids, base addresses) in scalar registers and scalar arithmetic
@@ -179,7 +177,7 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
     // word-major bitmaps: the kUnionRows row slots of one bitmap word are contiguous (slots past the
     // head's row count were cleared by the selection kernel), so a lane ORs its word over rows with
     // 16-byte loads at constant offsets: one memory latency, no per-row addressing
-    const uint32_t* maps = uni.rowmaps + (size_t)head * words * kUnionRows;
+    const uint32_t* maps = uni.rowmaps + (size_t)head * union_region_words(sh.rows_max, words);
     // (the loads of up to four groups of 64 words are issued before the first is used: taken one
     // group at a time, each group costs a memory round trip of its own - 8192 pages are four groups)
     constexpr int kGroupsInFlight = 4;
@@ -843,6 +841,37 @@ __global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep
   }
 }
 
+template <int D, int GP, int R, bool SPLIT_PAGES, int NBUF, int NWAVE = 4, bool LDS_TILES = false, bool F16V = false,
+          bool UNION = false>
+__global__ __launch_bounds__(64 * NWAVE) void attn_mfma_kernel(AttnPrepared prep, int nchunk, int nrbg, Shape sh, KvView kv,
+                                                        Partials part, float scale_log2e, int m_lo, int m_hi,
+                                                        UnionInKernel uni) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  attn_mfma_body<D, GP, R, SPLIT_PAGES, NBUF, NWAVE, LDS_TILES, F16V, UNION>(prep, nchunk, nrbg, sh, kv, part, scale_log2e,
+                                                                            m_lo, m_hi, uni, lds);
+}
+
+// The split-pages shape with the union built in the kernel, for launches whose row counts only the
+// device knows (threshold / cumulative-mass selection): every (sequence, KV head) runs the body
+// compiled for its own number of 16-row tiles, read from the count the selection kernel left, so a
+// head with a few active rows does not pay for the 64 the launch has to allow.  Heads with more than
+// 64 rows are not served here (m_hi).
+template <int D, int GP>
+__global__ __launch_bounds__(256) void attn_mfma_rows_kernel(AttnPrepared prep, int nchunk, Shape sh, KvView kv, Partials part,
+                                                             float scale_log2e, int m_lo, int m_hi, UnionInKernel uni) {
+  extern __shared__ __attribute__((aligned(16))) float lds[];
+  const int M = __builtin_amdgcn_readfirstlane(prep.mrows[blockIdx.z * sh.Hkv + blockIdx.y]);
+  if (M <= 0 || M > kUnionRows) return;
+  if (M <= 16)
+    attn_mfma_body<D, GP, 1, true, 2, 4, false, false, true>(prep, nchunk, 1, sh, kv, part, scale_log2e, m_lo, m_hi, uni, lds);
+  else if (M <= 32)
+    attn_mfma_body<D, GP, 2, true, 2, 4, false, false, true>(prep, nchunk, 1, sh, kv, part, scale_log2e, m_lo, m_hi, uni, lds);
+  else if (M <= 48)
+    attn_mfma_body<D, GP, 3, true, 2, 4, false, false, true>(prep, nchunk, 1, sh, kv, part, scale_log2e, m_lo, m_hi, uni, lds);
+  else
+    attn_mfma_body<D, GP, 4, true, 2, 4, false, false, true>(prep, nchunk, 1, sh, kv, part, scale_log2e, m_lo, m_hi, uni, lds);
+}
+
 // Builds the prepared inputs of attn_mfma_kernel when the selection kernel has not done so
 // (stand-alone losa_sparse_attn, and the dense initialisation): resolves the page list
 // (logical ids, or every page when sel_pages is NULL) to entries and gathers the query rows
@@ -950,6 +979,20 @@ template <int D, int GP>
 static hipError_t launch_dg(hipStream_t st, const KvView& kv, const Shape& sh, int batch, const AttnPrepared& prep,
                             int nchunk, int rows_upper, const Partials& part, hipEvent_t e0, hipEvent_t e1, int m_lo,
                             int m_hi, const UnionInKernel* uni, int many_rows) {
+  if (uni && uni->rowmaps && uni->rows_on_device) {   // ... and takes every head's row-tile count from the device
+    const size_t lds_bytes = (4 * MergeSlot<D, 4>::kFloats + kUnionShared) * sizeof(float);
+    auto kern = attn_mfma_rows_kernel<D, GP>;
+    static bool attr_set = false;   // per instantiation
+    if (lds_bytes > 48 * 1024 && !attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)lds_bytes);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    kern<<<dim3(nchunk, sh.Hkv, batch), 256, lds_bytes, st>>>(prep, nchunk, sh, kv, part, sh.sm_scale * 1.4426950408889634f,
+                                                              m_lo, m_hi, *uni);
+    return hipGetLastError();
+  }
   if (uni && uni->rowmaps) {   // the kernel builds the union from the row bitmaps itself
     if (rows_upper <= 16) return launch_one<D, GP, 1, true, 4, false, false, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi, *uni);
     if (rows_upper <= 32) return launch_one<D, GP, 2, true, 4, false, false, true>(st, kv, sh, batch, prep, nchunk, part, e0, e1, m_lo, m_hi, *uni);

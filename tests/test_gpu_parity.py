@@ -294,6 +294,63 @@ def test_empty_active_set_is_a_no_op():
         rig.close()
 
 
+@pytest.mark.parametrize("union_in_attention", [1, 0], ids=["union-in-attention", "union-in-selection"])
+def test_device_side_counts_on_blocks_of_at_most_64_rows(union_in_attention):
+    """Threshold and cumulative-mass selection leave the row count on the device.  A block that cannot
+    have more than 64 query rows per KV head (16 tokens x 4 query heads per KV head here) is still
+    served by the bitmaps-only selection and the attention kernel's own union, shaped by the upper
+    bound; checked against the oracle with few, many, all and no tokens active."""
+    w = synth.config(0).replace(B=16, Hq=8, Hkv=2, d=128, g=16, n_active=3, batch=3, seq_lens=(2500, 16, 911),
+                                topk_pages=5, T=4, outliers="lognormal", name="small-block")
+    r = Rig(w, tuning={L.LOSA_TUNE_UNION_IN_ATTENTION: union_in_attention})
+    try:
+        check_page_bounds(r)
+        run_steps_end_to_end(r, range(w.T), orc.SEL_THRESHOLD, 0.01, w.topk_pages)
+        run_steps_end_to_end(r, [1, 2], orc.SEL_MASS, 0.5, w.topk_pages)
+        run_steps_end_to_end(r, [3], orc.SEL_MASS, 1.0, w.topk_pages)         # every token with a positive score
+        run_steps_end_to_end(r, [1], orc.SEL_THRESHOLD, 1e-9, w.topk_pages)   # every token
+        blk = r.blk
+        before_o, before_l = blk.o_p.clone(), blk.lse_p.clone()
+        L.losa_step(r.ctx, r.layer.kv, 2, blk.h[2], blk.h[1], blk.q[2], orc.SEL_THRESHOLD, 1e9, w.topk_pages,
+                    blk.o_p, blk.lse_p, blk.mask, blk.sel_count)                # no token
+        torch.cuda.synchronize()
+        assert torch.equal(blk.o_p, before_o) and torch.equal(blk.lse_p, before_l)
+        assert int(blk.mask.sum()) == 0 and int(blk.sel_count.sum()) == 0
+        assert r.near_ties <= 2
+    finally:
+        r.close()
+
+
+def _more_active_tokens(inp):
+    """Sequence 1 gets 20 and sequence 2 exactly 16 tokens whose hidden states change a lot going into
+    steps 1 and 2 (their previous states with the sign flipped), sequence 0 keeps its 3."""
+    B = inp.w.B
+    for b, count in ((1, 20), (2, 16)):
+        mine = sorted({int(x) for t in (1, 2) for x in inp.picked[t, b]})   # the generator's own active tokens count too
+        mine += [x for x in range(B) if x not in mine][:count - len(mine)]
+        for t in (1, 2):
+            for tok in mine:
+                inp.h[t][b * B + tok] = inp.h[t - 1][b * B + tok] ^ np.uint16(0x8000)   # bfloat16 bits: the sign flips
+
+
+@pytest.mark.parametrize("union_in_attention", [1, 0], ids=["union-in-attention", "union-in-selection"])
+def test_device_side_counts_mixing_few_and_many_rows(union_in_attention):
+    """Threshold selection on a block of 128 query rows per KV head where the sequences of one launch
+    end up on different paths: 12 rows (bitmaps, one row tile), 80 rows (union list, many-row shape)
+    and exactly 64 rows (bitmaps, four row tiles)."""
+    w = synth.config(0).replace(B=32, Hq=8, Hkv=2, d=128, g=16, n_active=3, batch=3, seq_lens=(1500, 2200, 700),
+                                topk_pages=6, T=3, outliers="lognormal", name="mixed-rows")
+    r = Rig(w, mutate=_more_active_tokens, tuning={L.LOSA_TUNE_UNION_IN_ATTENTION: union_in_attention})
+    try:
+        check_page_bounds(r)
+        run_steps_end_to_end(r, range(w.T), orc.SEL_THRESHOLD, 0.01, w.topk_pages)
+        counts = r.blk.mask.view(w.batch, w.B).sum(dim=1).tolist()
+        assert counts == [3, 20, 16], counts   # 12, 80 and 64 rows: the three paths were taken
+        assert r.near_ties <= 2
+    finally:
+        r.close()
+
+
 def _random_workload(seed: int):
     rng = np.random.Generator(np.random.Philox(seed))
     B = int(rng.choice([16, 32, 48, 64]))
