@@ -556,7 +556,7 @@ template <int E, int NT, bool MULTI>
 __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, const int32_t* __restrict__ active_count,
                                                            const float* __restrict__ scores, int topk, SelectOut out,
                                                            int rpw) {
-  // A workgroup selects for rpw consecutive query rows, one after the other (the next row's
+  // A workgroup selects for up to rpw query rows, one after the other (the next row's
   // scores travel while the current row is selected).  rpw is 1 unless the grid would not fit
   // the machine in one round: a second round of workgroups costs more than a second row.
   // MULTI = false is the one-row form (rpw == 1) without the loop's register cost.
@@ -566,7 +566,11 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
   __shared__ uint32_t ubits[WORDS];     // union of the head's rows (used by the workgroup that builds it)
   __shared__ int s_last;
   __shared__ int scan[17];
-  const int r_first = blockIdx.x * rpw, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+  // A workgroup's rows are r_first, r_first + r_step, ...: dealt round-robin over the row workgroups, so
+  // that when the grid was sized for more rows than exist (a count only the device knows) the rows
+  // that do exist still spread over as many workgroups as possible.
+  const int r_step = MULTI ? (int)gridDim.x - 1 : 1;
+  const int r_first = blockIdx.x, j = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
   const int head = b * sh.Hkv + j;
   const int p_first_all = tid * E;
   const int p_first = p_first_all;
@@ -660,9 +664,9 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     ubits[w] = 0u;
   }
   if (tid < 256) rl.hist[tid] = 0u;
-  const int r_end = MULTI ? min(r_first + rpw, M) : r_first + 1;   // rows [r_first, r_end) are this workgroup's
+  const int r_end = MULTI ? M : r_first + 1;
 #pragma unroll 1
-  for (int r = r_first; r < r_end; ++r) {
+  for (int r = r_first; r < r_end; r += r_step) {
     // Per-thread constants are made opaque once per row: otherwise everything derived from them
     // (bit masks, predicates, addresses) is computed once ahead of the loop and kept in registers
     // across it, which costs half the kernel's occupancy.
@@ -674,7 +678,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     uint32_t key[E];
 #pragma unroll
     for (int i = 0; i < E; ++i) key[i] = i < nmine ? order_key(raw[i]) : 0u;
-    if (r + 1 < r_end) load_row(raw, r + 1);   // the next row's scores, on their way during this row's selection
+    if (r + r_step < r_end) load_row(raw, r + r_step);   // the next row's scores, on their way during this row's selection
 
     const bool all = Kp >= P;
     uint32_t prefix;
@@ -732,7 +736,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
       for (int w = tid; w < words; w += NT)
         __hip_atomic_store(&myrow[w], w < WORDS ? rowbits[w] : 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (r + 1 < r_end) {
+    if (r + r_step < r_end) {
       // the row bitmap has been read out (the stores above take their data at issue): clear the
       // LDS state of the next row; its first barrier (inside radix_kth) orders these writes
       __syncthreads();
@@ -741,7 +745,7 @@ __global__ __launch_bounds__(NT) void select_pages_kernel(KvView kv, Shape sh, c
     }
   }
   if (out.bitmaps_only && M <= kUnionRows) return;
-  const int rows_done = r_end - r_first;
+  const int rows_done = (r_end - 1 - r_first) / r_step + 1;
   __builtin_amdgcn_s_waitcnt(0);
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
   __syncthreads();
