@@ -27,6 +27,13 @@ def test_c1_full_32k():
     _run(synth.config(1).replace(T=4), range(4))
 
 
+def test_c1_every_denoising_step_of_a_block():
+    """All 16 steps of a C1 block in a row (dense initialisation, then 15 sparse steps on the state the
+    previous ones left): rows that are never active keep their initial values bit for bit, active rows
+    follow the oracle step by step."""
+    _run(synth.config(1), range(16))
+
+
 def test_c3_full_128k():
     _run(synth.config(3).replace(T=3), range(3))
 
