@@ -371,7 +371,7 @@ def _random_workload(seed: int):
                                    name=f"random-{seed}")
 
 
-@pytest.mark.parametrize("seed", list(range(32)) + [416, 488, 785, 789, 853])   # the last five: shapes that once caught a matrix-result read hazard
+@pytest.mark.parametrize("seed", list(range(64)) + [416, 488, 785, 789, 853])   # the last five: shapes that once caught a matrix-result read hazard
 def test_random_shapes_end_to_end(seed):
     """Seeded random head / block / page / batch shapes and prefix lengths (some shorter than a
     page or empty), dense initialisation then sparse steps in a randomly chosen selection mode,
