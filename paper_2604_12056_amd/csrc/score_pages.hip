@@ -329,7 +329,7 @@ __global__ __launch_bounds__(256) void page_scores_mfma_kernel(KvView kv, Shape 
         if (rr < nrows) {
           float* dst = out_base + (size_t)(r0 + rr) * sh.max_pages + p0t + 4 * qd;
           if (vec_ok) {
-            *reinterpret_cast<f32x4_t*>(dst) = acc;
+            __builtin_nontemporal_store(acc, reinterpret_cast<f32x4_t*>(dst));
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)

@@ -795,15 +795,17 @@ __device__ __forceinline__ void attn_mfma_body(AttnPrepared prep, int nchunk, in
         if (rg < M) {
           const size_t prow = item * part.rows + rg;
           if (W == 0 && qd == 0) {
-            part.m[prow] = m_all;
-            part.l[prow] = l_all;
+            // (streaming stores: the partials are read once, by the next launch; leaving them out of the
+            // caches' write-back at the kernel's end measured 0.3 us per step at 48 MB launches)
+            __builtin_nontemporal_store(m_all, &part.m[prow]);
+            __builtin_nontemporal_store(l_all, &part.l[prow]);
           }
 #pragma unroll
           for (int k = 0; k < NTW; ++k) {
             f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int w = 0; w < 4; ++w) acc += ov[mt][k][w] * wgt[w];
-            *reinterpret_cast<f32x4_t*>(part.o + prow * D + (W * NTW + k) * 16 + qd * 4) = acc;
+            __builtin_nontemporal_store(acc, reinterpret_cast<f32x4_t*>(part.o + prow * D + (W * NTW + k) * 16 + qd * 4));
           }
         }
       }
