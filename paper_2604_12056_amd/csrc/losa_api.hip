@@ -43,7 +43,11 @@ __global__ __launch_bounds__(256) void calibration_read_kernel(const uint4* __re
     for (int i = lane; i < tile16; i += 64) {
       uint4 v[4];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) v[k] = src[k][i];
+      for (int k = 0; k < 4; ++k) {   // streaming loads, as the attention kernel reads its tiles
+        typedef uint32_t cr_u32x4 __attribute__((ext_vector_type(4)));
+        const cr_u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const cr_u32x4*>(src[k] + i));
+        v[k] = make_uint4(x[0], x[1], x[2], x[3]);
+      }
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const bool live = t0 + k * nwaves < ntiles;   // (the repeat of the last tile is read but not counted)

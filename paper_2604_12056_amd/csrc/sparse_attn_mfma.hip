@@ -353,11 +353,13 @@ __device__ __forceinline__ void attn_mfma_body(AttnPrepared prep, int nchunk, in
     }
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      t.k[0][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(k0 + ks * 32 + qd * 8));
-      t.k[1][ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(k1 + ks * 32 + qd * 8));
+      // (streaming loads: a key / value tile is read once per step, and keeping it out of the caches'
+      // allocation measured 1 us at C1 and 10 us at C4 per step)
+      t.k[0][ks] = __builtin_bit_cast(bf16x8_t, __builtin_nontemporal_load(reinterpret_cast<const u32x4v_t*>(k0 + ks * 32 + qd * 8)));
+      t.k[1][ks] = __builtin_bit_cast(bf16x8_t, __builtin_nontemporal_load(reinterpret_cast<const u32x4v_t*>(k1 + ks * 32 + qd * 8)));
     }
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) t.v[nt] = *reinterpret_cast<const uint4*>(vp + nt * 16 * GP);
+    for (int nt = 0; nt < NT; ++nt) t.v[nt] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4v_t*>(vp + nt * 16 * GP)));
   };
 
   // Exponentials are taken against a reference point m_run that is allowed to lag the true
